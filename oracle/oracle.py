@@ -1,0 +1,184 @@
+"""ctypes loader for the CPU oracle (oracle/fast_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  The product package never imports this module, and
+this module imports nothing from the product package.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fast_oracle.cpp")
+_LIB = os.path.join(_HERE, "libfast_oracle.so")
+
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_f64p = ctypes.POINTER(ctypes.c_double)
+
+
+def build(force=True):
+    """Compile the oracle with g++ (plain host code, no ROCm)."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+        return _LIB
+    subprocess.check_call(
+        ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-Wall", "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build()
+        L = ctypes.CDLL(_LIB)
+        L.oracle_aggregate.argtypes = [ctypes.c_int, ctypes.c_int, _i64p, _i64p, _i64p, _i64p]
+        L.oracle_aggregate.restype = ctypes.c_int
+        L.oracle_rebalance_tile.argtypes = [ctypes.c_int, _i64p, _i64p, _i64p]
+        L.oracle_rebalance_tile.restype = None
+        L.oracle_rebalance.argtypes = [ctypes.c_int, ctypes.c_int, _i64p, _i64p]
+        L.oracle_rebalance.restype = None
+        L.oracle_collapse.argtypes = [ctypes.c_int, ctypes.c_int, _i64p, _i64p]
+        L.oracle_collapse.restype = None
+        L.oracle_embed.argtypes = [ctypes.c_int, _i64p, _i64p]
+        L.oracle_embed.restype = ctypes.c_int64
+        L.oracle_decompose.argtypes = [ctypes.c_int, _i64p, _i64p, ctypes.c_int, _i32p, _i64p]
+        L.oracle_decompose.restype = ctypes.c_int
+        L.oracle_cost.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double,
+                                  _i64p, _i64p, _i64p, _i64p, ctypes.c_int, _i64p, _f64p, _f64p]
+        L.oracle_cost.restype = None
+        L.oracle_synthesize.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                        ctypes.c_double, _i64p, _i64p, _i32p, _i64p, ctypes.c_int,
+                                        _i32p, _f64p, _f64p, _i64p, _i64p]
+        L.oracle_synthesize.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _p64(a):
+    return a.ctypes.data_as(_i64p)
+
+
+def _p32(a):
+    return a.ctypes.data_as(_i32p)
+
+
+def _pf(a):
+    return a.ctypes.data_as(_f64p)
+
+
+def _c64(a):
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+def aggregate(S, G, traffic):
+    """-> (status, T[S,S], intra_out[N], intra_in[N])"""
+    N = S * G
+    traffic = _c64(traffic).reshape(N, N)
+    T = np.zeros((S, S), np.int64)
+    io = np.zeros(N, np.int64)
+    ii = np.zeros(N, np.int64)
+    st = lib().oracle_aggregate(S, G, _p64(traffic), _p64(T), _p64(io), _p64(ii))
+    return st, T, io, ii
+
+
+def rebalance_tile(r):
+    """row sums r[G] -> (X[G,G], targets[G])"""
+    r = _c64(r)
+    G = r.shape[0]
+    X = np.zeros((G, G), np.int64)
+    t = np.zeros(G, np.int64)
+    lib().oracle_rebalance_tile(G, _p64(r), _p64(X), _p64(t))
+    return X, t
+
+
+def rebalance(S, G, traffic):
+    N = S * G
+    traffic = _c64(traffic).reshape(N, N)
+    X = np.zeros((N, N), np.int64)
+    lib().oracle_rebalance(S, G, _p64(traffic), _p64(X))
+    return X
+
+
+def collapse(G, T):
+    T = _c64(T)
+    S = T.shape[0]
+    Q = np.zeros((S, S), np.int64)
+    lib().oracle_collapse(S, G, _p64(T), _p64(Q))
+    return Q
+
+
+def embed(Q):
+    """-> (L, A[S,S])"""
+    Q = _c64(Q)
+    S = Q.shape[0]
+    A = np.zeros((S, S), np.int64)
+    L = lib().oracle_embed(S, _p64(Q), _p64(A))
+    return int(L), A
+
+
+def decompose(Q, A, cap=None):
+    """-> (K, stages[K,S] int32, bytes[K,S] int64)"""
+    Q = _c64(Q)
+    A = _c64(A)
+    S = Q.shape[0]
+    cap = S * S if cap is None else cap
+    st = np.full((max(cap, 1), S), -7, np.int32)
+    by = np.full((max(cap, 1), S), -7, np.int64)
+    K = lib().oracle_decompose(S, _p64(Q), _p64(A), cap, _p32(st), _p64(by))
+    if K < 0:
+        return K, st[:0], by[:0]
+    return K, st[:K].copy(), by[:K].copy()
+
+
+def cost(S, G, bw_up, bw_out, T, X, io, ii, stage_bytes):
+    """-> (out4 = [T_pred, t0, t2, t_opt], extra3 = [t1, t3, t_exc])"""
+    T = _c64(T)
+    X = _c64(X)
+    io = _c64(io)
+    ii = _c64(ii)
+    by = _c64(stage_bytes).reshape(-1, S) if len(stage_bytes) else np.zeros((0, S), np.int64)
+    K = by.shape[0]
+    by = _c64(by if K else np.zeros((1, S), np.int64))
+    out4 = np.zeros(4, np.float64)
+    ex = np.zeros(3, np.float64)
+    lib().oracle_cost(S, G, bw_up, bw_out, _p64(T), _p64(X), _p64(io), _p64(ii), K, _p64(by),
+                      _pf(out4), _pf(ex))
+    return out4, ex
+
+
+class Plan:
+    """Result of synthesize() for one matrix."""
+    __slots__ = ("status", "K", "X", "stages", "stage_bytes", "time4", "extra3", "Q", "A")
+
+
+def synthesize(S, G, bw_up, bw_out, traffic, cap=None):
+    N = S * G
+    traffic = _c64(traffic).reshape(N, N)
+    cap = S * S if cap is None else cap
+    X = np.zeros((N, N), np.int64)
+    st = np.full((max(cap, 1), S), -7, np.int32)
+    by = np.full((max(cap, 1), S), -7, np.int64)
+    ns = np.zeros(1, np.int32)
+    out4 = np.zeros(4, np.float64)
+    ex = np.zeros(3, np.float64)
+    Q = np.zeros((S, S), np.int64)
+    A = np.zeros((S, S), np.int64)
+    lib().oracle_synthesize(S, G, bw_up, bw_out, _p64(traffic), _p64(X), _p32(st), _p64(by), cap,
+                            _p32(ns), _pf(out4), _pf(ex), _p64(Q), _p64(A))
+    p = Plan()
+    p.status = int(ns[0])
+    p.K = max(int(ns[0]), 0)
+    p.X = X
+    p.stages = st[:p.K].copy()
+    p.stage_bytes = by[:p.K].copy()
+    p.time4 = out4
+    p.extra3 = ex
+    p.Q = Q
+    p.A = A
+    return p
