@@ -1,0 +1,133 @@
+/*
+ * fast.h - C ABI of the MI355X (gfx950) batched All-to-All(v) schedule synthesiser.
+ *
+ * For each of B GPU-to-GPU traffic matrices of a two-tier cluster of S servers x G
+ * GPUs (N = S*G GPUs, GPU g = a*G + i is GPU i of server a), the library computes,
+ * entirely on the device:
+ *   1. the intra-server sender balancing of every cross-server tile and the
+ *      resulting lane-routing matrix (paper Section 4.1 "Mitigating sender skew",
+ *      Section 4.2 Step 1), together with the merged peer transfer that collapses
+ *      each tile to one per-lane server-level entry (Section 4.1 "Mitigating
+ *      receiver skew", Section 4.2 / Fig. 6);
+ *   2. the embedding of the server-level matrix into a scaled doubly stochastic
+ *      matrix and its Birkhoff decomposition into balanced, one-to-one scale-out
+ *      stages (Section 4.4 "Adapting an arbitrary matrix to a valid form" and
+ *      "Birkhoff's decomposition: overview"; Section 4.2);
+ *   3. the analytical two-tier completion time of the plan (Section 5.4 simulator;
+ *      Appendix, Theorems 1 and 2).
+ *
+ * Conventions.  All byte counts are int64 and non-negative; indices are int32;
+ * times are double seconds; bandwidths are double bytes/second per GPU
+ * (full duplex).  "device" pointers are HIP device memory on the device that was
+ * current when the plan was created; "host" pointers are ordinary host memory.
+ * No function takes or returns ownership of a caller's buffer.
+ *
+ * Return codes: 0 on success, otherwise one of the negative FAST_ERR_* values;
+ * on error nothing has been enqueued.
+ */
+#ifndef FAST_H_
+#define FAST_H_
+
+#include <stdint.h>
+#include <hip/hip_runtime_api.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FAST_OK                0
+#define FAST_ERR_INVALID_ARG  -1   /* NULL pointer, B < 0, S < 1, G < 1, bandwidth not finite or <= 0 */
+#define FAST_ERR_UNSUPPORTED  -2   /* S > FAST_MAX_SERVERS or G > FAST_MAX_GPUS_PER_SERVER */
+#define FAST_ERR_HIP          -3   /* a HIP runtime call failed */
+#define FAST_ERR_OOM          -4   /* the plan's device workspace could not be allocated */
+
+#define FAST_MAX_SERVERS          128
+#define FAST_MAX_GPUS_PER_SERVER  8
+
+/* Per-matrix status values stored in out_num_stages[b] instead of a stage count. */
+#define FAST_STATUS_NEGATIVE_ENTRY  -1  /* an off-diagonal traffic entry is negative */
+#define FAST_STATUS_STAGE_OVERFLOW  -2  /* more than fast_plan_max_stages() stages (cannot happen
+                                           while the Birkhoff bound S*S-2S+2 holds; a tripwire) */
+#define FAST_STATUS_INTERNAL        -3  /* no augmenting path found (impossible for a doubly
+                                           stochastic residual; a tripwire) */
+
+typedef struct fast_plan fast_plan_t;   /* opaque; owns a device workspace */
+
+/*
+ * Creates a plan for clusters of S servers x G GPUs with per-GPU scale-up bandwidth
+ * link_bw_up ("B_1" of the Appendix) and scale-out bandwidth link_bw_out ("B_2").
+ * The plan is bound to the HIP device current at this call.  *out_plan receives the
+ * plan; free it with fast_plan_destroy.  Requires 1 <= S <= FAST_MAX_SERVERS and
+ * 1 <= G <= FAST_MAX_GPUS_PER_SERVER.
+ */
+int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_plan_t **out_plan);
+
+/* Stage capacity per matrix that the output buffers must provide: S*S (a safe
+ * bound; Section 4.4 "Number of stages" gives S*S - 2S + 2).  -1 if plan is NULL. */
+int fast_plan_max_stages(const fast_plan_t *plan);
+
+/*
+ * Synthesises the schedules of B traffic matrices.  All work is enqueued on
+ * `stream` (the plan's device must be current) and the call returns without
+ * synchronising; outputs are valid once the stream has drained.  The plan's
+ * workspace is grown on demand (the only allocation this call may make) and is
+ * reused by the next call, so calls on one plan must be stream-ordered.
+ *
+ *  traffic            device, [B][N][N] row-major; traffic[b][g][h] = bytes GPU g sends to
+ *                     GPU h (row = sender, Section 4.1 "Example setup").  The GPU diagonal
+ *                     g == h is ignored.  Read only.
+ *  out_rebalance      device, [B][N][N]; lane-routing matrix X of the sender balancing
+ *                     (Section 4.1): X[(a,i)][(d,k)] = bytes of GPU (a,i)'s traffic for server
+ *                     d that cross scale-out on lane k, i.e. leave from GPU (a,k) and arrive
+ *                     at its peer (d,k).  k == i: kept by the GPU; k != i: handed to (a,k)
+ *                     over scale-up first.  Lane loads are floor/ceil(T[a][d]/G) with the
+ *                     remainder on the lowest lanes; surplus is poured into deficit in
+ *                     ascending GPU index.  Intra-server tiles (d == a) are zero.
+ *  out_stages         device, [B][max_stages][S]; out_stages[b][s][a] = destination server of
+ *                     source server a in scale-out stage s, or -1 if a sends no real bytes in
+ *                     that stage.  In a stage, destinations of active servers are distinct
+ *                     (one-to-one) and GPU (a,k) talks only to GPU (dest,k) (Section 4.2,
+ *                     Step 2).  Rows s >= K are left untouched.
+ *  out_stage_bytes    device, [B][max_stages][S]; real bytes per lane that server a sends to
+ *                     out_stages[b][s][a] in stage s (0 where the destination is -1).
+ *  out_num_stages     device, [B]; number of stages K >= 0 of matrix b, or a negative
+ *                     FAST_STATUS_* value, in which case the other outputs of that matrix
+ *                     are unspecified.
+ *  out_predicted_time device, [B][4] = { T_pred, t0, t2, t_opt } in seconds:
+ *                     t0 = balancing, t2 = scale-out stages (sum of stage weights / B_out),
+ *                     T_pred = t0 + t1 + t2 + t3 (+ exposed redistribution when
+ *                     link_bw_up < (G-1)*link_bw_out) with t1 = intra-server portion and
+ *                     t3 = last stage's redistribution (Appendix, proof of Theorem 2, the
+ *                     four terms evaluated on the actual plan); t_opt = Theorem 1.
+ *
+ * Results are a deterministic function of each matrix alone: independent of B, of the
+ * position in the batch and of launch geometry.  B == 0 is valid and does nothing.
+ */
+int fast_synthesize_batched(fast_plan_t *plan, int B,
+                            const int64_t *traffic,
+                            int64_t *out_rebalance,
+                            int32_t *out_stages,
+                            int64_t *out_stage_bytes,
+                            int32_t *out_num_stages,
+                            double *out_predicted_time,
+                            hipStream_t stream);
+
+/*
+ * Per-kernel timing for measurement.  With enable != 0 every following
+ * fast_synthesize_batched call records HIP events on its stream around its three
+ * kernels (aggregation + balancing, decomposition, cost).  fast_plan_last_kernel_ms
+ * waits for the last such call to finish and writes the three durations in
+ * milliseconds to host array out_ms[3]; it returns FAST_ERR_INVALID_ARG if timing was
+ * not enabled or no call has been made.
+ */
+int fast_plan_set_timing(fast_plan_t *plan, int enable);
+int fast_plan_last_kernel_ms(fast_plan_t *plan, float *out_ms);
+
+/* Frees the plan and its workspace.  Work enqueued with it must have finished.
+ * NULL is a no-op. */
+void fast_plan_destroy(fast_plan_t *plan);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FAST_H_ */

@@ -1,0 +1,166 @@
+"""Thin ctypes binding of libfast.so (the C ABI of include/fast.h).
+
+Argument marshalling only: every step of the synthesis runs in the library's HIP
+kernels.  There is no CPU fallback: if libfast.so is missing or a call fails, an
+exception is raised.  PyTorch is used for device memory and streams.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfast.so")
+
+FAST_OK = 0
+FAST_ERR_INVALID_ARG = -1
+FAST_ERR_UNSUPPORTED = -2
+FAST_ERR_HIP = -3
+FAST_ERR_OOM = -4
+FAST_MAX_SERVERS = 128
+FAST_MAX_GPUS_PER_SERVER = 8
+FAST_STATUS_NEGATIVE_ENTRY = -1
+FAST_STATUS_STAGE_OVERFLOW = -2
+FAST_STATUS_INTERNAL = -3
+
+EXPORTS = ("fast_plan_create", "fast_plan_max_stages", "fast_synthesize_batched",
+           "fast_plan_set_timing", "fast_plan_last_kernel_ms", "fast_plan_destroy")
+
+_lib = None
+
+
+class FastError(RuntimeError):
+    def __init__(self, what, code):
+        super().__init__(f"{what} failed with code {code}")
+        self.code = code
+
+
+def lib():
+    """Loads libfast.so (built by `python -m paper_2505_09764_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: run `python -m paper_2505_09764_amd.build` first "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp = ctypes.c_void_p
+        L.fast_plan_create.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                       ctypes.c_double, ctypes.POINTER(vp)]
+        L.fast_plan_create.restype = ctypes.c_int
+        L.fast_plan_max_stages.argtypes = [vp]
+        L.fast_plan_max_stages.restype = ctypes.c_int
+        L.fast_synthesize_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp]
+        L.fast_synthesize_batched.restype = ctypes.c_int
+        L.fast_plan_set_timing.argtypes = [vp, ctypes.c_int]
+        L.fast_plan_set_timing.restype = ctypes.c_int
+        L.fast_plan_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+        L.fast_plan_last_kernel_ms.restype = ctypes.c_int
+        L.fast_plan_destroy.argtypes = [vp]
+        L.fast_plan_destroy.restype = None
+        _lib = L
+    return _lib
+
+
+# ---- the C entry points under their own names -------------------------------
+def fast_plan_create(S, G, link_bw_up, link_bw_out):
+    """-> opaque plan handle (ctypes.c_void_p).  Raises FastError."""
+    h = ctypes.c_void_p()
+    rc = lib().fast_plan_create(int(S), int(G), float(link_bw_up), float(link_bw_out),
+                                ctypes.byref(h))
+    if rc != FAST_OK:
+        raise FastError("fast_plan_create", rc)
+    return h
+
+
+def fast_plan_max_stages(plan):
+    return lib().fast_plan_max_stages(plan)
+
+
+def fast_synthesize_batched(plan, B, traffic, out_rebalance, out_stages, out_stage_bytes,
+                            out_num_stages, out_predicted_time, stream):
+    """Raw call: every buffer argument is a device address (int), stream a hipStream_t (int)."""
+    rc = lib().fast_synthesize_batched(plan, int(B), traffic, out_rebalance, out_stages,
+                                       out_stage_bytes, out_num_stages, out_predicted_time, stream)
+    if rc != FAST_OK:
+        raise FastError("fast_synthesize_batched", rc)
+
+
+def fast_plan_set_timing(plan, enable):
+    rc = lib().fast_plan_set_timing(plan, int(bool(enable)))
+    if rc != FAST_OK:
+        raise FastError("fast_plan_set_timing", rc)
+
+
+def fast_plan_last_kernel_ms(plan):
+    out = (ctypes.c_float * 3)()
+    rc = lib().fast_plan_last_kernel_ms(plan, out)
+    if rc != FAST_OK:
+        raise FastError("fast_plan_last_kernel_ms", rc)
+    return [float(out[0]), float(out[1]), float(out[2])]
+
+
+def fast_plan_destroy(plan):
+    lib().fast_plan_destroy(plan)
+
+
+# ---- convenience wrapper over torch tensors ---------------------------------
+class Outputs:
+    """Device tensors receiving the plans of one batch."""
+
+    def __init__(self, B, S, G, max_stages, device):
+        import torch
+        N = S * G
+        self.rebalance = torch.empty((B, N, N), dtype=torch.int64, device=device)
+        self.stages = torch.empty((B, max_stages, S), dtype=torch.int32, device=device)
+        self.stage_bytes = torch.empty((B, max_stages, S), dtype=torch.int64, device=device)
+        self.num_stages = torch.empty((B,), dtype=torch.int32, device=device)
+        self.predicted_time = torch.empty((B, 4), dtype=torch.float64, device=device)
+
+
+class Synthesizer:
+    """Owns one plan; synthesize() enqueues on the current torch stream."""
+
+    def __init__(self, S, G, link_bw_up, link_bw_out, device="cuda:0"):
+        import torch
+        self.S, self.G = int(S), int(G)
+        self.device = torch.device(device)
+        with torch.cuda.device(self.device):
+            self.plan = fast_plan_create(S, G, link_bw_up, link_bw_out)
+        self.max_stages = fast_plan_max_stages(self.plan)
+
+    def alloc_outputs(self, B):
+        return Outputs(B, self.S, self.G, self.max_stages, self.device)
+
+    def synthesize(self, traffic, out=None):
+        import torch
+        N = self.S * self.G
+        if traffic.dtype != torch.int64 or traffic.dim() != 3 or tuple(traffic.shape[1:]) != (N, N):
+            raise ValueError(f"traffic must be int64 [B, {N}, {N}]")
+        if not traffic.is_cuda or traffic.device != self.device or not traffic.is_contiguous():
+            raise ValueError("traffic must be a contiguous tensor on the plan's device")
+        B = traffic.shape[0]
+        if out is None:
+            out = self.alloc_outputs(B)
+        with torch.cuda.device(self.device):
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+            fast_synthesize_batched(self.plan, B, traffic.data_ptr(), out.rebalance.data_ptr(),
+                                    out.stages.data_ptr(), out.stage_bytes.data_ptr(),
+                                    out.num_stages.data_ptr(), out.predicted_time.data_ptr(),
+                                    stream)
+        return out
+
+    def set_timing(self, enable):
+        fast_plan_set_timing(self.plan, enable)
+
+    def last_kernel_ms(self):
+        return fast_plan_last_kernel_ms(self.plan)
+
+    def close(self):
+        if self.plan is not None:
+            fast_plan_destroy(self.plan)
+            self.plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

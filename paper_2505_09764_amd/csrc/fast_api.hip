@@ -1,0 +1,230 @@
+// Host side of the C ABI declared in include/fast.h: argument checks, the plan's
+// device workspace, and the three kernel launches of one synthesis call.
+#include "fast.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <new>
+
+#include "k1_rebalance.hpp"
+#include "k2_birkhoff.hpp"
+#include "k3_cost.hpp"
+
+using fastk::i64;
+
+struct fast_plan {
+    int S, G;
+    double bw_up, bw_out;
+    int device;
+    int max_stages;
+    // device workspace for `cap_B` matrices
+    int cap_B;
+    i64* wsT;      // [B][S][S]  server-to-server totals
+    i64* wsQ;      // [B][S][S]  per-lane server-level matrix
+    i64* wsPart;   // [B][S][K1_PART]
+    i64* wsC;      // [B][max_stages] stage weights
+    // timing
+    int timing;
+    bool timed_call;
+    hipEvent_t ev[4];
+};
+
+namespace {
+
+void free_workspace(fast_plan* p) {
+    if (p->wsT) (void)hipFree(p->wsT);
+    p->wsT = p->wsQ = p->wsPart = p->wsC = nullptr;
+    p->cap_B = 0;
+}
+
+int grow_workspace(fast_plan* p, int B) {
+    if (B <= p->cap_B) return FAST_OK;
+    free_workspace(p);
+    const size_t S = p->S;
+    const size_t nT = (size_t)B * S * S, nPart = (size_t)B * S * fastk::K1_PART,
+                 nC = (size_t)B * p->max_stages;
+    i64* base = nullptr;
+    if (hipMalloc(&base, (2 * nT + nPart + nC) * sizeof(i64)) != hipSuccess) {
+        (void)hipGetLastError();
+        return FAST_ERR_OOM;
+    }
+    p->wsT = base;
+    p->wsQ = base + nT;
+    p->wsPart = p->wsQ + nT;
+    p->wsC = p->wsPart + nPart;
+    p->cap_B = B;
+    return FAST_OK;
+}
+
+template <int G>
+void launch_k1(const fast_plan* p, int B, const i64* traffic, i64* X, hipStream_t stream) {
+    const dim3 grid(p->S, B), block(fastk::K1_THREADS);
+    const size_t lds = fastk::k1_lds_bytes(p->S, G);
+    const bool vec = (G % 2 == 0) && ((reinterpret_cast<uintptr_t>(traffic) |
+                                       reinterpret_cast<uintptr_t>(X)) % 16 == 0);
+    if constexpr (G % 2 == 0) {
+        if (vec) {
+            hipLaunchKernelGGL((fastk::k1_rebalance<G, true>), grid, block, lds, stream, traffic,
+                               X, p->wsT, p->wsQ, p->wsPart, p->S);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((fastk::k1_rebalance<G, false>), grid, block, lds, stream, traffic, X,
+                       p->wsT, p->wsQ, p->wsPart, p->S);
+}
+
+int next_pow2(int v) {
+    int n = 1;
+    while (n < v) n <<= 1;
+    return n;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_plan_t** out_plan) {
+    if (!out_plan) return FAST_ERR_INVALID_ARG;
+    *out_plan = nullptr;
+    if (S < 1 || G < 1) return FAST_ERR_INVALID_ARG;
+    if (!std::isfinite(link_bw_up) || !std::isfinite(link_bw_out) || link_bw_up <= 0.0 ||
+        link_bw_out <= 0.0)
+        return FAST_ERR_INVALID_ARG;
+    if (S > FAST_MAX_SERVERS || G > FAST_MAX_GPUS_PER_SERVER) return FAST_ERR_UNSUPPORTED;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return FAST_ERR_HIP;
+    }
+    fast_plan* p = new (std::nothrow) fast_plan();
+    if (!p) return FAST_ERR_OOM;
+    p->S = S;
+    p->G = G;
+    p->bw_up = link_bw_up;
+    p->bw_out = link_bw_out;
+    p->device = dev;
+    p->max_stages = S * S;
+    p->cap_B = 0;
+    p->wsT = p->wsQ = p->wsPart = p->wsC = nullptr;
+    p->timing = 0;
+    p->timed_call = false;
+    for (auto& e : p->ev) e = nullptr;
+
+    // The decomposition kernel keeps the S x S residual in LDS: up to 130 KiB of the
+    // CU's 160 KiB, which has to be requested explicitly above 64 KiB.
+    const int lds2 = (int)fastk::k2_lds_bytes(S);
+    hipError_t e = hipSuccess;
+    if (S > 64)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::k2_birkhoff<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds2);
+    else if (lds2 > 48 * 1024)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::k2_birkhoff<1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds2);
+    if (e == hipSuccess && link_bw_up < (double)(G - 1) * link_bw_out)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::k3_cost),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)(next_pow2(p->max_stages) * sizeof(i64)));
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        delete p;
+        return FAST_ERR_HIP;
+    }
+    *out_plan = p;
+    return FAST_OK;
+}
+
+int fast_plan_max_stages(const fast_plan_t* plan) { return plan ? plan->max_stages : -1; }
+
+int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64_t* out_rebalance,
+                            int32_t* out_stages, int64_t* out_stage_bytes, int32_t* out_num_stages,
+                            double* out_predicted_time, hipStream_t stream) {
+    if (!p || B < 0) return FAST_ERR_INVALID_ARG;
+    if (B == 0) return FAST_OK;
+    if (!traffic || !out_rebalance || !out_stages || !out_stage_bytes || !out_num_stages ||
+        !out_predicted_time)
+        return FAST_ERR_INVALID_ARG;
+    if (B > 65535) return FAST_ERR_UNSUPPORTED;     // grid.y limit of the first kernel
+    const int rc = grow_workspace(p, B);
+    if (rc != FAST_OK) return rc;
+
+    if (p->timing) {
+        for (auto& e : p->ev)
+            if (!e && hipEventCreate(&e) != hipSuccess) {
+                (void)hipGetLastError();
+                return FAST_ERR_HIP;
+            }
+        (void)hipEventRecord(p->ev[0], stream);
+    }
+
+    const i64* tr = reinterpret_cast<const i64*>(traffic);
+    i64* X = reinterpret_cast<i64*>(out_rebalance);
+    switch (p->G) {
+        case 1: launch_k1<1>(p, B, tr, X, stream); break;
+        case 2: launch_k1<2>(p, B, tr, X, stream); break;
+        case 3: launch_k1<3>(p, B, tr, X, stream); break;
+        case 4: launch_k1<4>(p, B, tr, X, stream); break;
+        case 5: launch_k1<5>(p, B, tr, X, stream); break;
+        case 6: launch_k1<6>(p, B, tr, X, stream); break;
+        case 7: launch_k1<7>(p, B, tr, X, stream); break;
+        default: launch_k1<8>(p, B, tr, X, stream); break;
+    }
+    if (p->timing) (void)hipEventRecord(p->ev[1], stream);
+
+    const size_t lds2 = fastk::k2_lds_bytes(p->S);
+    i64* sb = reinterpret_cast<i64*>(out_stage_bytes);
+    if (p->S > 64)
+        hipLaunchKernelGGL((fastk::k2_birkhoff<2>), dim3(B), dim3(fastk::K2_THREADS), lds2, stream,
+                           p->wsQ, p->wsPart, out_stages, sb, out_num_stages, p->wsC, p->S,
+                           p->max_stages);
+    else
+        hipLaunchKernelGGL((fastk::k2_birkhoff<1>), dim3(B), dim3(fastk::K2_THREADS), lds2, stream,
+                           p->wsQ, p->wsPart, out_stages, sb, out_num_stages, p->wsC, p->S,
+                           p->max_stages);
+    if (p->timing) (void)hipEventRecord(p->ev[2], stream);
+
+    const bool slow_up = p->bw_up < (double)(p->G - 1) * p->bw_out;
+    const int sort_n = slow_up ? next_pow2(p->max_stages) : 0;
+    hipLaunchKernelGGL(fastk::k3_cost, dim3(B), dim3(fastk::K3_THREADS),
+                       (size_t)sort_n * sizeof(i64), stream, p->wsT, p->wsPart, p->wsC,
+                       out_num_stages, out_predicted_time, p->S, p->G, p->max_stages, p->bw_up,
+                       p->bw_out, sort_n);
+    if (p->timing) {
+        (void)hipEventRecord(p->ev[3], stream);
+        p->timed_call = true;
+    }
+    if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
+    return FAST_OK;
+}
+
+int fast_plan_set_timing(fast_plan_t* p, int enable) {
+    if (!p) return FAST_ERR_INVALID_ARG;
+    p->timing = enable ? 1 : 0;
+    if (!enable) p->timed_call = false;
+    return FAST_OK;
+}
+
+int fast_plan_last_kernel_ms(fast_plan_t* p, float* out_ms) {
+    if (!p || !out_ms || !p->timing || !p->timed_call) return FAST_ERR_INVALID_ARG;
+    if (hipEventSynchronize(p->ev[3]) != hipSuccess) {
+        (void)hipGetLastError();
+        return FAST_ERR_HIP;
+    }
+    for (int k = 0; k < 3; ++k)
+        if (hipEventElapsedTime(&out_ms[k], p->ev[k], p->ev[k + 1]) != hipSuccess) {
+            (void)hipGetLastError();
+            return FAST_ERR_HIP;
+        }
+    return FAST_OK;
+}
+
+void fast_plan_destroy(fast_plan_t* p) {
+    if (!p) return;
+    free_workspace(p);
+    for (auto& e : p->ev)
+        if (e) (void)hipEventDestroy(e);
+    delete p;
+}
+
+}  // extern "C"

@@ -1,0 +1,259 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle,
+element by element on the same seeded inputs.
+
+Bar: lane-routing matrix, stage count, stage destinations and stage bytes are
+bit-exact; predicted times agree to 1e-9 relative (they are expected to be
+identical, since both sides divide the same integers in the same order).
+"""
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+SENT32 = -77
+SENT64 = -7777
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def run_gpu(torch, S, G, bw_up, bw_out, traffic, prefill=True):
+    """traffic: numpy [B,N,N] or device tensor.  Returns host numpy outputs."""
+    from paper_2505_09764_amd.binding import Synthesizer
+    dev = torch.device("cuda:0")
+    t = traffic if isinstance(traffic, torch.Tensor) else torch.from_numpy(
+        np.ascontiguousarray(traffic, dtype=np.int64)).to(dev)
+    syn = Synthesizer(S, G, bw_up, bw_out, dev)
+    out = syn.alloc_outputs(t.shape[0])
+    if prefill:
+        out.rebalance.fill_(SENT64)
+        out.stages.fill_(SENT32)
+        out.stage_bytes.fill_(SENT64)
+        out.num_stages.fill_(SENT32)
+        out.predicted_time.fill_(-1.0)
+    syn.synthesize(t, out)
+    torch.cuda.synchronize()
+    res = dict(X=out.rebalance.cpu().numpy(), stages=out.stages.cpu().numpy(),
+               bytes=out.stage_bytes.cpu().numpy(), K=out.num_stages.cpu().numpy(),
+               time=out.predicted_time.cpu().numpy())
+    syn.close()
+    return res
+
+
+def compare_one(oracle, S, G, bw_up, bw_out, tr, res, b, check_untouched=True):
+    p = oracle.synthesize(S, G, bw_up, bw_out, tr)
+    K = int(res["K"][b])
+    assert K == p.status, f"matrix {b}: stage count / status {K} != oracle {p.status}"
+    if K < 0:
+        return p
+    assert np.array_equal(res["X"][b], p.X), f"matrix {b}: lane-routing matrix differs"
+    assert np.array_equal(res["stages"][b, :K], p.stages), f"matrix {b}: stage destinations differ"
+    assert np.array_equal(res["bytes"][b, :K], p.stage_bytes), f"matrix {b}: stage bytes differ"
+    if check_untouched:
+        assert (res["stages"][b, K:] == SENT32).all() and (res["bytes"][b, K:] == SENT64).all()
+    np.testing.assert_allclose(res["time"][b], p.time4, rtol=1e-9, atol=0.0)
+    return p
+
+
+def compare_batch(oracle, w_S, w_G, bw_up, bw_out, traffic, res, idx=None, threads=8):
+    idx = range(traffic.shape[0]) if idx is None else idx
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda b: compare_one(oracle, w_S, w_G, bw_up, bw_out, traffic[b], res, b),
+                    idx))
+
+
+# ----------------------------------------------------------------------------
+# the five benchmark configurations, full batch size, launch geometry of bench.py
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("ci", [1, 2, 3, 4])
+def test_config_full_batch(oracle, torch_cuda, ci):
+    from paper_2505_09764_amd import workloads as W
+    w = W.config(ci)
+    say(f"[parity] {w.name} S={w.S} G={w.G} B={w.B} seed={w.seed}")
+    dev_t = W.generate_device(w)
+    host_t = dev_t.cpu().numpy()
+    res = run_gpu(torch_cuda, w.S, w.G, w.bw_up, w.bw_out, dev_t)
+    assert (res["K"] >= 0).all()
+    compare_batch(oracle, w.S, w.G, w.bw_up, w.bw_out, host_t, res)
+
+
+def test_config5_full_batch(oracle, torch_cuda):
+    from paper_2505_09764_amd import workloads as W
+    w = W.config(5)
+    say(f"[parity] {w.name} S={w.S} G={w.G} B={w.B} seed={w.seed}")
+    dev_t = W.generate_device(w)
+    host_t = dev_t.cpu().numpy()
+    res = run_gpu(torch_cuda, w.S, w.G, w.bw_up, w.bw_out, dev_t)
+    assert (res["K"] > 0).all()
+    say("[parity] cfg5 GPU done, K range %d..%d; oracle on every matrix" %
+        (res["K"].min(), res["K"].max()))
+    compare_batch(oracle, w.S, w.G, w.bw_up, w.bw_out, host_t, res, threads=16)
+    # properties that hold at any size, from the definitions (two matrices: python loops)
+    for b in (0, w.B - 1):
+        K = int(res["K"][b])
+        H.check_rebalance(host_t[b], res["X"][b], w.S, w.G)
+        H.check_stages(host_t[b], w.S, w.G, res["stages"][b, :K], res["bytes"][b, :K])
+    # single-matrix call (B = 1) gives the same plan as inside the batch
+    one = run_gpu(torch_cuda, w.S, w.G, w.bw_up, w.bw_out, dev_t[7:8])
+    K = int(res["K"][7])
+    assert int(one["K"][0]) == K
+    assert np.array_equal(one["X"][0], res["X"][7])
+    assert np.array_equal(one["stages"][0, :K], res["stages"][7, :K])
+    assert np.array_equal(one["bytes"][0, :K], res["bytes"][7, :K])
+    assert np.array_equal(one["time"][0], res["time"][7])
+
+
+def test_generator_host_equals_device(torch_cuda):
+    from paper_2505_09764_amd import workloads as W
+    for ci, B in [(2, 5), (3, 2), (4, 4)]:
+        w = W.config(ci)
+        say(f"[gen] {w.name} B={B}")
+        assert np.array_equal(W.generate_device(w, B).cpu().numpy(), W.generate_host(w, B))
+
+
+# ----------------------------------------------------------------------------
+# shapes: every G, ragged S, both lane widths of the decomposition kernel
+# ----------------------------------------------------------------------------
+def _rand(rng, S, G, kind):
+    N = S * G
+    if kind == "uniform":
+        t = rng.integers(0, 100000, size=(N, N))
+    elif kind == "heavy":
+        t = (rng.pareto(1.1, size=(N, N)) * 1000).astype(np.int64)
+    elif kind == "sparse":
+        t = rng.integers(0, 1000, size=(N, N)) * (rng.random((N, N)) < 0.1)
+    elif kind == "big":
+        t = rng.integers(0, 1 << 40, size=(N, N))
+    else:
+        raise ValueError(kind)
+    t = t.astype(np.int64)
+    t[np.arange(N), np.arange(N)] = rng.integers(-3, 9, size=N)      # diagonal is ignored
+    return t
+
+
+SHAPES = [(1, 1), (1, 8), (2, 1), (2, 2), (3, 3), (5, 7), (7, 5), (9, 6), (16, 4), (33, 2),
+          (37, 3), (64, 2), (65, 1), (65, 8), (100, 3), (127, 2), (128, 1), (128, 4)]
+
+
+@pytest.mark.parametrize("S,G", SHAPES)
+def test_random_shapes(oracle, torch_cuda, S, G):
+    rng = np.random.default_rng(100 * S + G)
+    kinds = ["uniform", "heavy", "sparse", "big"]
+    B = 8 if S <= 64 else 4
+    tr = np.stack([_rand(rng, S, G, kinds[b % 4]) for b in range(B)])
+    say(f"[parity] random S={S} G={G} B={B} seed={100 * S + G}")
+    res = run_gpu(torch_cuda, S, G, 400e9, 50e9, tr)
+    compare_batch(oracle, S, G, 400e9, 50e9, tr, res)
+
+
+def test_degenerate_inputs(oracle, torch_cuda):
+    S, G = 6, 4
+    N = S * G
+    rng = np.random.default_rng(11)
+    zero = np.zeros((N, N), np.int64)
+    equal = np.full((N, N), 12345, np.int64)
+    hot = zero.copy()
+    hot[5, 17] = 1 << 33
+    onerow = zero.copy()
+    onerow[9, :] = rng.integers(1, 1 << 20, size=N)
+    onecol = zero.copy()
+    onecol[:, 2] = rng.integers(1, 1 << 20, size=N)
+    intra_only = zero.copy()
+    for a in range(S):
+        intra_only[a * G:(a + 1) * G, a * G:(a + 1) * G] = rng.integers(0, 99, size=(G, G))
+    near = rng.integers((1 << 40) - 1000, 1 << 40, size=(N, N)).astype(np.int64)
+    ones = (rng.random((N, N)) < 0.5).astype(np.int64)
+    adversarial = zero.copy()                      # Appendix: one GPU holds / receives everything
+    for a in range(S):
+        for d in range(S):
+            if a != d:
+                adversarial[a * G, d * G + 1] = rng.integers(1, 1 << 30)
+    tr = np.stack([zero, equal, hot, onerow, onecol, intra_only, near, ones, adversarial])
+    say(f"[parity] degenerate inputs S={S} G={G} B={len(tr)}")
+    res = run_gpu(torch_cuda, S, G, 400e9, 50e9, tr)
+    assert res["K"][0] == 0 and (res["time"][0] == 0).all()
+    assert res["K"][1] == S - 1
+    assert res["K"][5] == 0 and res["time"][5][2] == 0 and res["time"][5][0] > 0
+    compare_batch(oracle, S, G, 400e9, 50e9, tr, res)
+
+
+def test_negative_entry_status_is_per_matrix(oracle, torch_cuda):
+    S, G = 4, 8
+    rng = np.random.default_rng(5)
+    tr = np.stack([_rand(rng, S, G, "uniform") for _ in range(5)])
+    tr[1, 3, 20] = -1
+    tr[3, 31, 0] = -(1 << 40)
+    say("[parity] negative entries S=4 G=8 B=5")
+    res = run_gpu(torch_cuda, S, G, 400e9, 50e9, tr)
+    assert res["K"].tolist()[1] == -1 and res["K"].tolist()[3] == -1
+    compare_batch(oracle, S, G, 400e9, 50e9, tr, res)
+
+
+def test_slow_scale_up_exposes_redistribution(oracle, torch_cuda):
+    # B_up < (G-1) B_out: the sorted-stage term of the cost model is exercised
+    from paper_2505_09764_amd import workloads as W
+    w = W.config(3)
+    tr = W.generate_host(w, 4)
+    say("[parity] slow scale-up cost path, cfg3 B=4")
+    res = run_gpu(torch_cuda, w.S, w.G, 100e9, 50e9, tr)
+    compare_batch(oracle, w.S, w.G, 100e9, 50e9, tr, res)
+    p = oracle.synthesize(w.S, w.G, 100e9, 50e9, tr[0])
+    assert p.extra3[2] > 0
+    S, G = 128, 2                                     # largest sort (K up to S*S)
+    rng = np.random.default_rng(8)
+    tr = np.stack([_rand(rng, S, G, "heavy") for _ in range(2)])
+    res = run_gpu(torch_cuda, S, G, 10e9, 50e9, tr)
+    compare_batch(oracle, S, G, 10e9, 50e9, tr, res)
+
+
+def test_deterministic_and_position_independent(torch_cuda):
+    from paper_2505_09764_amd import workloads as W
+    w = W.config(3)
+    tr = W.generate_host(w, 6)
+    say("[parity] determinism, cfg3 B=6")
+    r1 = run_gpu(torch_cuda, w.S, w.G, w.bw_up, w.bw_out, tr)
+    r2 = run_gpu(torch_cuda, w.S, w.G, w.bw_up, w.bw_out, tr)
+    for k in r1:
+        assert np.array_equal(r1[k], r2[k])
+    perm = np.array([4, 0, 5, 2, 1, 3])
+    r3 = run_gpu(torch_cuda, w.S, w.G, w.bw_up, w.bw_out, tr[perm])
+    for k in r1:
+        assert np.array_equal(r1[k][perm], r3[k])
+
+
+def test_plan_reuse_and_b0(torch_cuda):
+    from paper_2505_09764_amd.binding import Synthesizer
+    from paper_2505_09764_amd import workloads as W
+    torch = torch_cuda
+    w = W.config(2)
+    syn = Synthesizer(w.S, w.G, w.bw_up, w.bw_out)
+    t_big = W.generate_device(w, 64)
+    t_small = t_big[:3].contiguous()
+    say("[parity] plan reuse: B=3, then B=64 (workspace grows), then B=3, then B=0")
+    o1 = syn.synthesize(t_small)
+    o2 = syn.synthesize(t_big)
+    o3 = syn.synthesize(t_small)
+    syn.synthesize(t_big[:0].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(o1.num_stages, o3.num_stages) and torch.equal(o1.rebalance, o3.rebalance)
+    assert torch.equal(o1.num_stages, o2.num_stages[:3])
+    assert torch.equal(o1.predicted_time, o2.predicted_time[:3])
+    syn.set_timing(True)
+    syn.synthesize(t_big)
+    ms = syn.last_kernel_ms()
+    assert len(ms) == 3 and all(m > 0 for m in ms)
+    syn.close()
