@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of batched All-to-All(v) schedule synthesis on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu]
+
+One step = one fast_synthesize_batched call (all three kernels) over one batch of
+seeded synthetic traffic matrices already resident in HBM.  Default workload: the
+largest configuration (128 servers x 8 GPUs, B = 64), the one the headline metric is
+quoted on.  Prints ONE JSON line:
+  value          schedules synthesised per second = B * steps / timed seconds
+  p50/p99_us_per_schedule   per-step time / B
+  kernels_ms     average duration of each kernel (HIP events on the launch stream)
+  roofline       the streaming kernel (aggregation + balancing) against HBM peak
+  stage_loop     the decomposition kernel, which is bound by its serial stage chain
+  cpu_baseline   the CPU oracle timed on this machine's host cores on a bounded sample
+  latency_b1     the same configuration at B = 1 (true single-matrix latency)
+"""
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak, GB/s
+
+
+def percentile(xs, q):
+    xs = sorted(xs)
+    if not xs:
+        return None
+    k = min(len(xs) - 1, max(0, int(round(q * (len(xs) - 1)))))
+    return xs[k]
+
+
+def time_steps(torch, syn, traffic, out, steps, warmup, per_kernel):
+    for _ in range(warmup):
+        syn.synthesize(traffic, out)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    if per_kernel:
+        syn.set_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record()
+    for k in range(steps):
+        syn.synthesize(traffic, out)
+        ev[k + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    if per_kernel:
+        syn.set_timing(False)
+    step_ms = [ev[k].elapsed_time(ev[k + 1]) for k in range(steps)]
+    total_ms = ev[0].elapsed_time(ev[steps])
+    kms = syn.kernel_ms() if per_kernel else []
+    return total_ms, step_ms, kms, wall
+
+
+def cpu_baseline(w, host_traffic, n_all, n_single):
+    """Oracle as it stands on this machine's host cores: all-core throughput with one
+    matrix per task, and single-thread time per schedule."""
+    from oracle import oracle as O
+    O.lib()
+    cores = min(os.cpu_count() or 1, 16)
+    n_all = min(n_all, host_traffic.shape[0])
+    n_single = min(n_single, host_traffic.shape[0])
+
+    def one(b):
+        t = time.perf_counter()
+        O.synthesize(w.S, w.G, w.bw_up, w.bw_out, host_traffic[b])
+        return time.perf_counter() - t
+
+    single = [one(b) for b in range(n_single)]
+    threads = min(cores, n_all)
+    t = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(one, range(n_all)))
+    wall = time.perf_counter() - t
+    return {
+        "value": n_all / wall, "unit": "schedules/s", "cores": threads, "kind": "oracle",
+        "sample": f"first {n_all} matrices of the batch, one matrix per task on {threads} "
+                  f"threads; single-thread time from the first {n_single}",
+        "single_thread_us_per_schedule_p50": percentile(single, 0.5) * 1e6,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5")
+    ap.add_argument("--batch", type=int, default=None, help="override the batch size B")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (matrices of a batch are "
+                 "independent and would be split across GPUs without any exchange); "
+                 "run with --gpus 1")
+
+    import torch
+    from paper_2505_09764_amd import binding, workloads as W
+    if not os.path.exists(binding.LIB_PATH):
+        sys.exit("bench.py: libfast.so is not built (python -m paper_2505_09764_amd.build)")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w = W.config(args.config)
+    B = w.B if args.batch is None else args.batch
+    S, G, N = w.S, w.G, w.N
+    traffic = W.generate_device(w, B, dev)
+    syn = binding.Synthesizer(S, G, w.bw_up, w.bw_out, dev)
+    out = syn.alloc_outputs(B)
+
+    total_ms, step_ms, kms, _ = time_steps(torch, syn, traffic, out, args.steps, args.warmup, True)
+    K = out.num_stages.cpu().numpy()
+    assert (K >= 0).all(), "a matrix failed to synthesise"
+    ms_per_step = total_ms / args.steps
+    per_sched_us = [m * 1e3 / B for m in step_ms]
+    k_avg = [sum(k[i] for k in kms) / len(kms) for i in range(3)] if kms else [None] * 3
+
+    # algorithmic bytes (what the method must move), per launch
+    k1_bytes = B * (2 * 8 * N * N + 2 * 8 * S * S + 8 * 4 * S)
+    k2_bytes = B * (8 * S * S) + int(K.sum()) * (12 * S + 8) + 4 * B
+    k3_bytes = B * (8 * S * S + 8 * 4 * S + 32) + 8 * int(K.sum())
+    k1_gbs = k1_bytes / (k_avg[0] * 1e-3) / 1e9
+    measured = None
+    prof = os.path.join(ROOT, "profiles", f"k1_rebalance_cfg{args.config}_hbm_traffic.json")
+    if os.path.exists(prof) and B == w.B:
+        measured = json.load(open(prof)).get("hbm_bytes_per_launch")
+
+    # true single-matrix latency of the same configuration
+    lat = None
+    if B > 1:
+        syn1 = binding.Synthesizer(S, G, w.bw_up, w.bw_out, dev)
+        t1 = traffic[:1].contiguous()
+        out1 = syn1.alloc_outputs(1)
+        n1 = max(5, min(args.steps, 20))
+        _, s1, k1ms, _ = time_steps(torch, syn1, t1, out1, n1, 2, True)
+        lat = {"p50_us": percentile(s1, 0.5) * 1e3, "p99_us": percentile(s1, 0.99) * 1e3,
+               "stages": int(out1.num_stages[0].item()),
+               "kernels_ms": [sum(k[i] for k in k1ms) / len(k1ms) for i in range(3)]}
+        syn1.close()
+
+    cpu = None
+    if not args.no_cpu:
+        host = traffic[:32].cpu().numpy()
+        cpu = cpu_baseline(w, host, n_all=32 if S >= 64 else 256, n_single=4 if S >= 64 else 32)
+
+    stages_total = int(K.sum())
+    result = {
+        "metric": "schedules_synthesized_per_sec",
+        "value": B * args.steps / (total_ms * 1e-3),
+        "unit": "schedules/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int64",
+        "data": "synthetic",
+        "config": {"workload": w.name, "S": S, "G": G, "N": N, "B": B, "seed": w.seed,
+                   "link_bw_up": w.bw_up, "link_bw_out": w.bw_out},
+        "p50_us_per_schedule": percentile(per_sched_us, 0.5),
+        "p99_us_per_schedule": percentile(per_sched_us, 0.99),
+        "stages_per_schedule_mean": stages_total / B,
+        "kernels_ms": {"k1_rebalance": k_avg[0], "k2_birkhoff": k_avg[1], "k3_cost": k_avg[2]},
+        "roofline": {"kernel": "k1_rebalance", "bound": "hbm", "achieved": k1_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k1_gbs / HBM_PEAK_GBS,
+                     "traffic": measured, "algorithmic_bytes": k1_bytes},
+        "stage_loop": {"kernel": "k2_birkhoff", "bound": "serial stage chain (latency)",
+                       "stages_per_sec_per_matrix": (K.max() / (k_avg[1] * 1e-3)),
+                       "ns_per_stage": k_avg[1] * 1e6 / K.max(),
+                       "achieved_GBs": k2_bytes / (k_avg[1] * 1e-3) / 1e9,
+                       "algorithmic_bytes": k2_bytes},
+        "end_to_end_GBs": (k1_bytes + k2_bytes + k3_bytes) / (ms_per_step * 1e-3) / 1e9,
+        "latency_b1": lat,
+        "cpu_baseline": cpu,
+    }
+    syn.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -113,15 +113,20 @@ int fast_synthesize_batched(fast_plan_t *plan, int B,
                             hipStream_t stream);
 
 /*
- * Per-kernel timing for measurement.  With enable != 0 every following
- * fast_synthesize_batched call records HIP events on its stream around its three
- * kernels (aggregation + balancing, decomposition, cost).  fast_plan_last_kernel_ms
- * waits for the last such call to finish and writes the three durations in
- * milliseconds to host array out_ms[3]; it returns FAST_ERR_INVALID_ARG if timing was
- * not enabled or no call has been made.
+ * Per-kernel timing for measurement.  fast_plan_set_timing(plan, 1) starts a new
+ * recording (dropping any earlier one): each following fast_synthesize_batched call,
+ * up to FAST_MAX_TIMED_CALLS of them, records HIP events on its stream around its
+ * three kernels (aggregation + balancing, decomposition, cost); further calls run
+ * untimed.  fast_plan_set_timing(plan, 0) stops recording and keeps what was recorded.
+ * fast_plan_timed_calls returns how many calls have been recorded (-1 if plan is NULL).
+ * fast_plan_kernel_ms waits for recorded call `call` (0-based) to finish and writes its
+ * three kernel durations in milliseconds to host array out_ms[3]; FAST_ERR_INVALID_ARG
+ * if there is no such recorded call.
  */
+#define FAST_MAX_TIMED_CALLS 256
 int fast_plan_set_timing(fast_plan_t *plan, int enable);
-int fast_plan_last_kernel_ms(fast_plan_t *plan, float *out_ms);
+int fast_plan_timed_calls(const fast_plan_t *plan);
+int fast_plan_kernel_ms(fast_plan_t *plan, int call, float *out_ms);
 
 /* Frees the plan and its workspace.  Work enqueued with it must have finished.
  * NULL is a no-op. */

@@ -22,7 +22,8 @@ FAST_STATUS_STAGE_OVERFLOW = -2
 FAST_STATUS_INTERNAL = -3
 
 EXPORTS = ("fast_plan_create", "fast_plan_max_stages", "fast_synthesize_batched",
-           "fast_plan_set_timing", "fast_plan_last_kernel_ms", "fast_plan_destroy")
+           "fast_plan_set_timing", "fast_plan_timed_calls", "fast_plan_kernel_ms",
+           "fast_plan_destroy")
 
 _lib = None
 
@@ -52,8 +53,10 @@ def lib():
         L.fast_synthesize_batched.restype = ctypes.c_int
         L.fast_plan_set_timing.argtypes = [vp, ctypes.c_int]
         L.fast_plan_set_timing.restype = ctypes.c_int
-        L.fast_plan_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
-        L.fast_plan_last_kernel_ms.restype = ctypes.c_int
+        L.fast_plan_timed_calls.argtypes = [vp]
+        L.fast_plan_timed_calls.restype = ctypes.c_int
+        L.fast_plan_kernel_ms.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
+        L.fast_plan_kernel_ms.restype = ctypes.c_int
         L.fast_plan_destroy.argtypes = [vp]
         L.fast_plan_destroy.restype = None
         _lib = L
@@ -90,11 +93,15 @@ def fast_plan_set_timing(plan, enable):
         raise FastError("fast_plan_set_timing", rc)
 
 
-def fast_plan_last_kernel_ms(plan):
+def fast_plan_timed_calls(plan):
+    return lib().fast_plan_timed_calls(plan)
+
+
+def fast_plan_kernel_ms(plan, call):
     out = (ctypes.c_float * 3)()
-    rc = lib().fast_plan_last_kernel_ms(plan, out)
+    rc = lib().fast_plan_kernel_ms(plan, int(call), out)
     if rc != FAST_OK:
-        raise FastError("fast_plan_last_kernel_ms", rc)
+        raise FastError("fast_plan_kernel_ms", rc)
     return [float(out[0]), float(out[1]), float(out[2])]
 
 
@@ -151,8 +158,9 @@ class Synthesizer:
     def set_timing(self, enable):
         fast_plan_set_timing(self.plan, enable)
 
-    def last_kernel_ms(self):
-        return fast_plan_last_kernel_ms(self.plan)
+    def kernel_ms(self):
+        """Per-kernel milliseconds of every recorded call -> list of [k1, k2, k3]."""
+        return [fast_plan_kernel_ms(self.plan, c) for c in range(fast_plan_timed_calls(self.plan))]
 
     def close(self):
         if self.plan is not None:

@@ -25,10 +25,10 @@ struct fast_plan {
     i64* wsQ;      // [B][S][S]  per-lane server-level matrix
     i64* wsPart;   // [B][S][K1_PART]
     i64* wsC;      // [B][max_stages] stage weights
-    // timing
+    // timing: four events per recorded call
     int timing;
-    bool timed_call;
-    hipEvent_t ev[4];
+    int n_timed;
+    hipEvent_t (*ev)[4];
 };
 
 namespace {
@@ -109,8 +109,8 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     p->cap_B = 0;
     p->wsT = p->wsQ = p->wsPart = p->wsC = nullptr;
     p->timing = 0;
-    p->timed_call = false;
-    for (auto& e : p->ev) e = nullptr;
+    p->n_timed = 0;
+    p->ev = nullptr;
 
     // The decomposition kernel keeps the S x S residual in LDS: up to 130 KiB of the
     // CU's 160 KiB, which has to be requested explicitly above 64 KiB.
@@ -149,13 +149,19 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
     const int rc = grow_workspace(p, B);
     if (rc != FAST_OK) return rc;
 
-    if (p->timing) {
-        for (auto& e : p->ev)
-            if (!e && hipEventCreate(&e) != hipSuccess) {
+    hipEvent_t* ev = nullptr;
+    if (p->timing && p->n_timed < FAST_MAX_TIMED_CALLS) {
+        if (!p->ev) {
+            p->ev = new (std::nothrow) hipEvent_t[FAST_MAX_TIMED_CALLS][4]();
+            if (!p->ev) return FAST_ERR_OOM;
+        }
+        ev = p->ev[p->n_timed];
+        for (int k = 0; k < 4; ++k)
+            if (!ev[k] && hipEventCreate(&ev[k]) != hipSuccess) {
                 (void)hipGetLastError();
                 return FAST_ERR_HIP;
             }
-        (void)hipEventRecord(p->ev[0], stream);
+        (void)hipEventRecord(ev[0], stream);
     }
 
     const i64* tr = reinterpret_cast<const i64*>(traffic);
@@ -170,7 +176,7 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
         case 7: launch_k1<7>(p, B, tr, X, stream); break;
         default: launch_k1<8>(p, B, tr, X, stream); break;
     }
-    if (p->timing) (void)hipEventRecord(p->ev[1], stream);
+    if (ev) (void)hipEventRecord(ev[1], stream);
 
     const size_t lds2 = fastk::k2_lds_bytes(p->S);
     i64* sb = reinterpret_cast<i64*>(out_stage_bytes);
@@ -182,7 +188,7 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
         hipLaunchKernelGGL((fastk::k2_birkhoff<1>), dim3(B), dim3(fastk::K2_THREADS), lds2, stream,
                            p->wsQ, p->wsPart, out_stages, sb, out_num_stages, p->wsC, p->S,
                            p->max_stages);
-    if (p->timing) (void)hipEventRecord(p->ev[2], stream);
+    if (ev) (void)hipEventRecord(ev[2], stream);
 
     const bool slow_up = p->bw_up < (double)(p->G - 1) * p->bw_out;
     const int sort_n = slow_up ? next_pow2(p->max_stages) : 0;
@@ -190,9 +196,9 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
                        (size_t)sort_n * sizeof(i64), stream, p->wsT, p->wsPart, p->wsC,
                        out_num_stages, out_predicted_time, p->S, p->G, p->max_stages, p->bw_up,
                        p->bw_out, sort_n);
-    if (p->timing) {
-        (void)hipEventRecord(p->ev[3], stream);
-        p->timed_call = true;
+    if (ev) {
+        (void)hipEventRecord(ev[3], stream);
+        ++p->n_timed;
     }
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     return FAST_OK;
@@ -201,18 +207,21 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
 int fast_plan_set_timing(fast_plan_t* p, int enable) {
     if (!p) return FAST_ERR_INVALID_ARG;
     p->timing = enable ? 1 : 0;
-    if (!enable) p->timed_call = false;
+    if (enable) p->n_timed = 0;
     return FAST_OK;
 }
 
-int fast_plan_last_kernel_ms(fast_plan_t* p, float* out_ms) {
-    if (!p || !out_ms || !p->timing || !p->timed_call) return FAST_ERR_INVALID_ARG;
-    if (hipEventSynchronize(p->ev[3]) != hipSuccess) {
+int fast_plan_timed_calls(const fast_plan_t* p) { return p ? p->n_timed : -1; }
+
+int fast_plan_kernel_ms(fast_plan_t* p, int call, float* out_ms) {
+    if (!p || !out_ms || call < 0 || call >= p->n_timed) return FAST_ERR_INVALID_ARG;
+    hipEvent_t* ev = p->ev[call];
+    if (hipEventSynchronize(ev[3]) != hipSuccess) {
         (void)hipGetLastError();
         return FAST_ERR_HIP;
     }
     for (int k = 0; k < 3; ++k)
-        if (hipEventElapsedTime(&out_ms[k], p->ev[k], p->ev[k + 1]) != hipSuccess) {
+        if (hipEventElapsedTime(&out_ms[k], ev[k], ev[k + 1]) != hipSuccess) {
             (void)hipGetLastError();
             return FAST_ERR_HIP;
         }
@@ -222,8 +231,12 @@ int fast_plan_last_kernel_ms(fast_plan_t* p, float* out_ms) {
 void fast_plan_destroy(fast_plan_t* p) {
     if (!p) return;
     free_workspace(p);
-    for (auto& e : p->ev)
-        if (e) (void)hipEventDestroy(e);
+    if (p->ev) {
+        for (int c = 0; c < FAST_MAX_TIMED_CALLS; ++c)
+            for (int k = 0; k < 4; ++k)
+                if (p->ev[c][k]) (void)hipEventDestroy(p->ev[c][k]);
+        delete[] p->ev;
+    }
     delete p;
 }
 
