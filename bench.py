@@ -96,6 +96,10 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size B")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of 512 MiB (read 512 MiB + write "
+                         "512 MiB) so a counter profile of this run contains a kernel of known "
+                         "HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (matrices of a batch are "
@@ -117,6 +121,14 @@ def main():
     traffic = W.generate_device(w, B, dev)
     syn = binding.Synthesizer(S, G, w.bw_up, w.bw_out, dev)
     out = syn.alloc_outputs(B)
+
+    if args.calibrate_copy:
+        src = torch.arange(64 * 1024 * 1024, dtype=torch.int64, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     total_ms, step_ms, kms, _ = time_steps(torch, syn, traffic, out, args.steps, args.warmup, True)
     K = out.num_stages.cpu().numpy()
