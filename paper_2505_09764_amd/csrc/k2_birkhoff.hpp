@@ -3,20 +3,32 @@
 // One wavefront (64 lanes) per traffic matrix.  The stage loop of Birkhoff's
 // decomposition (paper Section 4.4 "Birkhoff's decomposition: overview") is a
 // chain of dependent steps - find a perfect matching, take the smallest matched
-// entry as the stage weight, subtract, repair the matching - so the design goal is
-// the shortest possible dependent path per stage, not memory throughput:
+// entry as the stage weight, subtract, repair the matching - and a generic
+// matrix needs about (S-1)^2 stages, so the design goal is the fewest
+// instructions on the dependent path of one stage, not memory throughput (one
+// wavefront issues an instruction every 5 to 8 cycles whatever its kind):
 //   * a single wavefront owns the matrix, so no step needs a workgroup barrier;
 //     lane l owns rows l, l+64 and columns l, l+64 (S <= 128);
 //   * the residual matrix R = Q + A lives in LDS (S*S int64) and is only touched
 //     when the matching changes: the residual of each row's matched cell is held
 //     in a register and written back when the row is re-matched;
-//   * the support of R is kept as one S-bit row mask per column in registers, so a
-//     breadth-first level of the augmenting-path search is two AND/compare
-//     operations per lane plus wave ballots; the frontier is a wave-uniform mask;
+//   * the support of R is kept as one S-bit row mask per column in registers;
+//     frontiers, visited sets and the set of unmatched columns are wave-uniform
+//     bit masks, so one breadth-first level is a few AND/compare operations per
+//     lane plus ballots, and "does the frontier reach an unmatched column" is a
+//     scalar test on that column's mask;
+//   * parents are not stored: the parent of a column is recomputed while the
+//     augmenting path is flipped, as the lowest set bit of (its support mask AND
+//     the frontier of the level that reached it);
+//   * almost every stage exhausts exactly one cell (r0, f) and is repaired by a
+//     path of at most three levels; that case runs as straight-line code, every
+//     other case goes through the general search;
 //   * the virtual matrix A of the embedding (Section 4.4 "Adapting an arbitrary
 //     matrix to a valid form") is never stored: pouring row deficits into column
 //     deficits in ascending order makes A[a][d] the overlap of two prefix-sum
-//     intervals (plus the diagonal term), recomputed when a cell gets matched.
+//     intervals (plus the diagonal term); cells that hold virtual bytes are
+//     flagged in bit 63 of their LDS word and the overlap is recomputed only
+//     when such a cell gets matched.
 //
 // Canonical choices that make the result a function of the matrix alone (the
 // paper leaves them open): level-synchronous search from one unmatched row, the
@@ -34,25 +46,52 @@
 
 namespace fastk {
 
+typedef unsigned int u32;
+
 constexpr int K2_THREADS = 64;
+constexpr u64 VFLAG = 1ull << 63;      // LDS word flag: the cell holds virtual bytes
 
 inline size_t k2_lds_bytes(int S) {
-    return (size_t)S * S * sizeof(i64) + (size_t)2 * S * sizeof(i64);
+    // R[S][S], column deficit intervals PC[S], EC[S], frontier history [(S+2)][2]
+    return (size_t)S * S * 8 + (size_t)2 * S * 8 + (size_t)(S + 2) * 16;
 }
 
-__device__ __forceinline__ int rdlane(int v, int lane) {
-    return __builtin_amdgcn_readlane(v, lane);
+__device__ __forceinline__ u64 ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+__device__ __forceinline__ u32 rdl(u32 v, int lane) { return (u32)__builtin_amdgcn_readlane(v, lane); }
+__device__ __forceinline__ u64 rdl64(u64 v, int lane) {
+    return ((u64)rdl((u32)(v >> 32), lane) << 32) | rdl((u32)v, lane);
 }
 
-__device__ __forceinline__ u64 wave_min_u64(u64 v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const u64 o = __shfl_xor(v, off, 64);
-        v = o < v ? o : v;
-    }
-    return v;
+// tells the compiler that a value is the same in every lane
+__device__ __forceinline__ u64 uniform64(u64 x) {
+    return ((u64)(u32)__builtin_amdgcn_readfirstlane((u32)(x >> 32)) << 32) |
+           (u64)(u32)__builtin_amdgcn_readfirstlane((u32)x);
 }
 
+template <int CTRL>
+__device__ __forceinline__ u32 dpp_min(u32 v) {
+    const u32 o = __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+    return o < v ? o : v;
+}
+// min over the 64 lanes, result wave-uniform
+__device__ __forceinline__ u32 wave_min_u32(u32 v) {
+    v = dpp_min<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_min<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_min<0x141>(v);   // row_half_mirror
+    v = dpp_min<0x140>(v);   // row_mirror
+    const u32 a = rdl(v, 0), b = rdl(v, 16), c = rdl(v, 32), d = rdl(v, 48);
+    const u32 ab = a < b ? a : b, cd = c < d ? c : d;
+    return ab < cd ? ab : cd;
+}
+// 64-bit minimum as two 32-bit passes: high words first, then the low words of
+// the lanes that hold the smallest high word
+__device__ __forceinline__ u64 wave_min_u64(u64 x) {
+    const u32 hi = (u32)(x >> 32);
+    const u32 mhi = wave_min_u32(hi);
+    const u32 lo = hi == mhi ? (u32)x : 0xFFFFFFFFu;
+    const u32 mlo = wave_min_u32(lo);
+    return ((u64)mhi << 32) | mlo;
+}
 __device__ __forceinline__ i64 wave_max_i64(i64 v) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -61,8 +100,6 @@ __device__ __forceinline__ i64 wave_max_i64(i64 v) {
     }
     return v;
 }
-
-// inclusive prefix sum over the 64 lanes
 __device__ __forceinline__ i64 wave_scan_incl(i64 v, int lane) {
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -79,9 +116,10 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             int32_t* __restrict__ out_stages, i64* __restrict__ out_bytes,
             int32_t* __restrict__ out_num, i64* __restrict__ wsC, int S, int max_stages) {
     extern __shared__ __align__(16) unsigned char k2_smem[];
-    i64* R = reinterpret_cast<i64*>(k2_smem);     // [S][S]
-    i64* PC = R + (size_t)S * S;                  // [S] start of column d's deficit interval
-    i64* EC = PC + S;                             // [S] end of it
+    u64* R = reinterpret_cast<u64*>(k2_smem);
+    i64* PC = reinterpret_cast<i64*>(R + (size_t)S * S);
+    i64* EC = PC + S;
+    u64* Fh = reinterpret_cast<u64*>(EC + S);       // [level][2]
     const int b = blockIdx.x;
     const int lane = threadIdx.x;
 
@@ -89,15 +127,14 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     {
         int bad = 0;
         for (int a = lane; a < S; a += 64) bad |= (int)wsPart[((size_t)b * S + a) * K1_PART + 2];
-        if (__ballot(bad != 0)) {
+        if (ballot(bad != 0)) {
             if (lane == 0) out_num[b] = -1;
             return;
         }
     }
-
     // ---- load Q (per-lane bytes of every server pair, diagonal zero)
     const i64* Qg = wsQ + (size_t)b * S * S;
-    for (int e = lane; e < S * S; e += 64) R[e] = Qg[e];
+    for (int e = lane; e < S * S; e += 64) R[e] = (u64)Qg[e];
     __syncthreads();
 
     // ---- row / column sums, L = heaviest line (Section 4.4)
@@ -109,17 +146,17 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         csum[k] = 0;
         if (x < S) {
             for (int j = 0; j < S; ++j) {
-                int d = j + x;                     // rotated so that lanes hit different banks
+                int d = j + x;
                 d = d >= S ? d - S : d;
-                rsum[k] += R[(size_t)x * S + d];
-                csum[k] += R[(size_t)j * S + x];
+                rsum[k] += (i64)R[(size_t)x * S + d];
+                csum[k] += (i64)R[(size_t)j * S + x];
             }
         }
     }
     i64 lmax = 0;
 #pragma unroll
     for (int k = 0; k < NR; ++k) lmax = max(lmax, max(rsum[k], csum[k]));
-    const i64 L = wave_max_i64(lmax);
+    const i64 L = (i64)uniform64((u64)wave_max_i64(lmax));
     if (L == 0) {
         if (lane == 0) out_num[b] = 0;
         return;
@@ -159,124 +196,215 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     for (int k = 0; k < NR; ++k) {
         const int x = lane + 64 * k;
         if (x < S) {
-            if (diag[k] > 0) R[(size_t)x * S + x] += diag[k];
+            if (diag[k] > 0) R[(size_t)x * S + x] = (R[(size_t)x * S + x] + (u64)diag[k]) | VFLAG;
             if (ER[k] > PR[k]) {
                 for (int j = 0; j < S; ++j) {
                     int d = j + x;
                     d = d >= S ? d - S : d;
                     const i64 l = max(PR[k], PC[d]);
                     const i64 h = min(ER[k], EC[d]);
-                    if (h > l) R[(size_t)x * S + d] += h - l;
+                    if (h > l) R[(size_t)x * S + d] = (R[(size_t)x * S + d] + (u64)(h - l)) | VFLAG;
                 }
             }
         }
     }
     __syncthreads();
 
-    // ---- support masks: bit a of cm[k] is set while R[a][column] > 0
-    u64 cmLo[NR], cmHi[NR];
+    // support masks: bit a of cm[k][a/64] set while R[a][column lane+64k] > 0
+    u64 cm[NR][NR];
 #pragma unroll
     for (int k = 0; k < NR; ++k) {
         const int x = lane + 64 * k;
-        cmLo[k] = 0;
-        cmHi[k] = 0;
+#pragma unroll
+        for (int w = 0; w < NR; ++w) cm[k][w] = 0;
         if (x < S) {
             for (int a = 0; a < S; ++a) {
-                const bool pos = R[(size_t)a * S + x] > 0;
-                if (a < 64) cmLo[k] |= (u64)pos << a;
-                else cmHi[k] |= (u64)pos << (a - 64);
+                const u64 pos = (R[(size_t)a * S + x] & ~VFLAG) != 0;
+#pragma unroll
+                for (int w = 0; w < NR; ++w)
+                    if ((a >> 6) == w) cm[k][w] |= pos << (a & 63);
             }
         }
     }
 
-    int mr[NR], mc[NR], loaded[NR], par[NR];
-    i64 rv[NR], av[NR];
+    int mr[NR], loaded[NR];
+    i64 rv[NR], rl[NR];
+    u64 vfl[NR];
 #pragma unroll
     for (int k = 0; k < NR; ++k) {
         mr[k] = -1;
-        mc[k] = -1;
         loaded[k] = -1;
-        par[k] = 0;
         rv[k] = 0;
-        av[k] = 0;
+        rl[k] = 0;
+        vfl[k] = 0;
+    }
+    u64 FREEC[NR];     // unmatched columns (wave-uniform)
+#pragma unroll
+    for (int w = 0; w < NR; ++w) {
+        const int n = S - 64 * w;
+        FREEC[w] = n >= 64 ? ~0ull : (n <= 0 ? 0ull : ((1ull << n) - 1));
     }
 
-    // select / update slot `s` (wave-uniform) of a per-lane pair
-    auto sel = [&](const int (&v)[NR], int s) -> int {
-        if constexpr (NR == 2) return s ? v[1] : v[0];
-        else return v[0];
+    // cm of column d (uniform) as uniform words
+    auto col_mask = [&](int d, u64 (&out)[NR]) {
+        const int dl = d & 63;
+#pragma unroll
+        for (int w = 0; w < NR; ++w) {
+            if constexpr (NR == 2) out[w] = (d >> 6) ? rdl64(cm[1][w], dl) : rdl64(cm[0][w], dl);
+            else out[w] = rdl64(cm[0][w], dl);
+        }
+    };
+    auto lowest = [&](const u64 (&m)[NR]) -> int {
+        if constexpr (NR == 2) return m[0] ? __builtin_ctzll(m[0]) : 64 + __builtin_ctzll(m[1]);
+        else return __builtin_ctzll(m[0]);
+    };
+    auto any = [&](const u64 (&m)[NR]) -> bool {
+        if constexpr (NR == 2) return (m[0] | m[1]) != 0;
+        else return m[0] != 0;
     };
 
-    // Augmenting path from unmatched row r0 (wave-uniform).  Returns false if none.
     auto augment = [&](int r0) -> bool {
-        u64 Flo = r0 < 64 ? 1ull << r0 : 0;
-        u64 Fhi = r0 >= 64 ? 1ull << (r0 - 64) : 0;
-        bool vis[NR];
+        u64 F[NR], VIS[NR];
 #pragma unroll
-        for (int k = 0; k < NR; ++k) vis[k] = false;
-        int dstar = -1;
+        for (int w = 0; w < NR; ++w) {
+            F[w] = (r0 >> 6) == w ? 1ull << (r0 & 63) : 0;
+            VIS[w] = 0;
+        }
+        int nfree = 0;
+#pragma unroll
+        for (int w = 0; w < NR; ++w) nfree += __builtin_popcountll(FREEC[w]);
+        const bool few = nfree <= 2;
+        int level = 1, dstar = -1, a = -1;
         for (;;) {
-            bool isnew[NR], isfree[NR];
+            if (few) {
+                // few unmatched columns: test each against the frontier with scalar work
+                u64 fr[NR];
+#pragma unroll
+                for (int w = 0; w < NR; ++w) fr[w] = FREEC[w];
+                while (any(fr)) {
+                    const int f = lowest(fr);
+                    u64 cmf[NR];
+                    col_mask(f, cmf);
+#pragma unroll
+                    for (int w = 0; w < NR; ++w) cmf[w] &= F[w];
+                    if (any(cmf)) {
+                        dstar = f;
+                        a = lowest(cmf);
+                        break;
+                    }
+#pragma unroll
+                    for (int w = 0; w < NR; ++w)
+                        if ((f >> 6) == w) fr[w] &= ~(1ull << (f & 63));
+                }
+                if (dstar >= 0) break;
+            }
+            u64 N[NR];
 #pragma unroll
             for (int k = 0; k < NR; ++k) {
-                const u64 cl = cmLo[k] & Flo;
-                const u64 ch = NR == 2 ? (cmHi[k] & Fhi) : 0;
-                isnew[k] = !vis[k] && ((cl | ch) != 0);
-                if (isnew[k]) {
-                    par[k] = cl ? __builtin_ctzll(cl) : 64 + __builtin_ctzll(ch);
-                    vis[k] = true;
+                u64 cand = 0;
+#pragma unroll
+                for (int w = 0; w < NR; ++w) cand |= cm[k][w] & F[w];
+                N[k] = ballot(cand != 0) & ~VIS[k];
+            }
+            if (!few) {
+                u64 fr[NR];
+#pragma unroll
+                for (int w = 0; w < NR; ++w) fr[w] = N[w] & FREEC[w];
+                if (any(fr)) {
+                    dstar = lowest(fr);
+                    u64 cmf[NR];
+                    col_mask(dstar, cmf);
+#pragma unroll
+                    for (int w = 0; w < NR; ++w) cmf[w] &= F[w];
+                    a = lowest(cmf);
+                    break;
                 }
-                isfree[k] = isnew[k] && mc[k] < 0;
             }
-            const u64 f0 = __ballot(isfree[0]);
-            const u64 f1 = NR == 2 ? __ballot(isfree[NR - 1]) : 0;
-            if (f0 | f1) {
-                dstar = f0 ? __builtin_ctzll(f0) : 64 + __builtin_ctzll(f1);
-                break;
+            if (!any(N)) return false;
+#pragma unroll
+            for (int w = 0; w < NR; ++w) VIS[w] |= N[w];
+            if (level >= 2 && lane == 0) {
+#pragma unroll
+                for (int w = 0; w < NR; ++w) Fh[level * 2 + w] = F[w];
             }
-            const u64 n0 = __ballot(isnew[0]);
-            const u64 n1 = NR == 2 ? __ballot(isnew[NR - 1]) : 0;
-            if ((n0 | n1) == 0) return false;
-            // next frontier: the rows matched to the newly reached columns
-            bool inF[NR];
 #pragma unroll
             for (int k = 0; k < NR; ++k) {
                 const int m = mr[k];
-                inF[k] = m >= 0 && (((m < 64 ? n0 : n1) >> (m & 63)) & 1);
+                u64 word;
+                if constexpr (NR == 2) word = m < 64 ? N[0] : N[1];
+                else word = N[0];
+                F[k] = ballot(m >= 0 && ((word >> (m & 63)) & 1));
             }
-            Flo = __ballot(inF[0]);
-            Fhi = NR == 2 ? __ballot(inF[NR - 1]) : 0;
+            ++level;
         }
-        // flip the path back to r0
+        // flip the path: column dstar <- row a <- its old column <- ... <- r0
         int d = dstar;
         for (int hops = 0;; ++hops) {
-            if (hops > S) return false;            // cannot happen: a path visits each row once
-            const int a = rdlane(sel(par, d >> 6), d & 63);
-            const int prev = rdlane(sel(mr, a >> 6), a & 63);
+            if (hops > S) return false;
+            int prev;
+            if constexpr (NR == 2) prev = (a >> 6) ? (int)rdl(mr[1], a & 63) : (int)rdl(mr[0], a & 63);
+            else prev = (int)rdl(mr[0], a & 63);
 #pragma unroll
             for (int k = 0; k < NR; ++k) {
-                if (lane + 64 * k == a) mr[k] = d;
-                if (lane + 64 * k == d) mc[k] = a;
+                mr[k] = (lane + 64 * k == a) ? d : mr[k];
             }
             if (a == r0) break;
             d = prev;
+            --level;
+            u64 Fl[NR];
+            if (level == 1) {
+#pragma unroll
+                for (int w = 0; w < NR; ++w) Fl[w] = (r0 >> 6) == w ? 1ull << (r0 & 63) : 0;
+            } else {
+#pragma unroll
+                for (int w = 0; w < NR; ++w) {
+                    const u64 x = Fh[level * 2 + w];
+                    Fl[w] = ((u64)(u32)__builtin_amdgcn_readfirstlane((u32)(x >> 32)) << 32) |
+                            (u64)(u32)__builtin_amdgcn_readfirstlane((u32)x);
+                }
+            }
+            u64 cmd[NR];
+            col_mask(d, cmd);
+#pragma unroll
+            for (int w = 0; w < NR; ++w) cmd[w] &= Fl[w];
+            a = lowest(cmd);
         }
+#pragma unroll
+        for (int w = 0; w < NR; ++w)
+            if ((dstar >> 6) == w) FREEC[w] &= ~(1ull << (dstar & 63));
         return true;
     };
 
-    // Make rv / av describe the cell each row is matched to now.
     auto sync_matched = [&]() {
+        bool needv[NR];
 #pragma unroll
         for (int k = 0; k < NR; ++k) {
             const int a = lane + 64 * k;
-            if (a < S && mr[k] != loaded[k]) {
-                if (loaded[k] >= 0 && rv[k] > 0) R[(size_t)a * S + loaded[k]] = rv[k];
-                const int d = mr[k];
-                rv[k] = R[(size_t)a * S + d];
-                const i64 l = max(PR[k], PC[d]);
-                const i64 h = min(ER[k], EC[d]);
-                av[k] = (h > l ? h - l : 0) + (d == a ? diag[k] : 0);
-                loaded[k] = d;
+            needv[k] = false;
+            if (mr[k] != loaded[k]) {
+                if (rv[k] > 0) R[(size_t)a * S + loaded[k]] = (u64)rv[k] | vfl[k];
+                const u64 x = R[(size_t)a * S + mr[k]];
+                vfl[k] = x & VFLAG;
+                rv[k] = (i64)(x & ~VFLAG);
+                rl[k] = rv[k];
+                loaded[k] = mr[k];
+                needv[k] = vfl[k] != 0;
+            }
+        }
+        bool anyv = false;
+#pragma unroll
+        for (int k = 0; k < NR; ++k) anyv = anyv || ballot(needv[k]) != 0;
+        if (anyv) {
+#pragma unroll
+            for (int k = 0; k < NR; ++k) {
+                if (needv[k]) {
+                    const int a = lane + 64 * k;
+                    const int d = mr[k];
+                    const i64 l = max(PR[k], PC[d]);
+                    const i64 h = min(ER[k], EC[d]);
+                    const i64 av = (h > l ? h - l : 0) + (d == a ? diag[k] : 0);
+                    rl[k] = rv[k] > av ? rv[k] - av : 0;
+                }
             }
         }
     };
@@ -289,55 +417,177 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         return;
     }
     sync_matched();
+#pragma unroll
+    for (int k = 0; k < NR; ++k)
+        if (lane + 64 * k >= S) rv[k] = INT64_MAX;     // never the minimum, never zero
 
-    // ---- stage loop
-    const size_t obase = (size_t)b * max_stages;
+    int32_t* stg = out_stages + (size_t)b * max_stages * S;
+    i64* byt = out_bytes + (size_t)b * max_stages * S;
+    i64* cw = wsC + (size_t)b * max_stages;
     i64 Lrem = L;
     int s = 0;
+    u32 off = lane;
+    int lid[NR];
+    u32 rowbase[NR];
+#pragma unroll
+    for (int k = 0; k < NR; ++k) {
+        lid[k] = lane + 64 * k;
+        rowbase[k] = (u32)(lane + 64 * k) * (u32)S;
+    }
+    // mr of a uniform row
+    auto mr_of = [&](int a) -> int {
+        if constexpr (NR == 2) return (int)rdl((u32)((a & 64) ? mr[1] : mr[0]), a & 63);
+        else return (int)rdl((u32)mr[0], a);
+    };
+    auto set_mr = [&](int a, int d) {
+#pragma unroll
+        for (int k = 0; k < NR; ++k) mr[k] = lid[k] == a ? d : mr[k];
+    };
+    // columns (as a uniform mask per column slot) adjacent to any row of F
+    auto expand = [&](const u64 (&F)[NR], u64 (&N)[NR]) {
+#pragma unroll
+        for (int k = 0; k < NR; ++k) {
+            u64 cand = 0;
+#pragma unroll
+            for (int w = 0; w < NR; ++w) cand |= cm[k][w] & F[w];
+            N[k] = ballot(cand != 0);
+        }
+    };
+    // rows (uniform mask per row slot) whose matched column is in N
+    auto rows_matched_into = [&](const u64 (&N)[NR], u64 (&F)[NR]) {
+#pragma unroll
+        for (int k = 0; k < NR; ++k) {
+            const int m = mr[k];
+            u64 word;
+            if constexpr (NR == 2) word = m < 64 ? N[0] : N[1];
+            else word = N[0];
+            F[k] = ballot(m >= 0 && ((word >> (m & 63)) & 1));
+        }
+    };
+
     for (;;) {
         if (s >= max_stages) { status = -2; break; }
-        u64 mine = ~0ull;
-#pragma unroll
-        for (int k = 0; k < NR; ++k)
-            if (lane + 64 * k < S) mine = min(mine, (u64)rv[k]);
+        u64 mine = (u64)rv[0];
+        if constexpr (NR == 2) mine = (u64)rv[1] < mine ? (u64)rv[1] : mine;
         const i64 c = (i64)wave_min_u64(mine);
+        u64 Z[NR];
         bool zero[NR];
 #pragma unroll
         for (int k = 0; k < NR; ++k) {
-            const int a = lane + 64 * k;
-            zero[k] = false;
-            if (a < S) {
-                const i64 realleft = rv[k] > av[k] ? rv[k] - av[k] : 0;
-                const i64 real = min(c, realleft);
-                out_stages[(obase + s) * S + a] = real > 0 ? mr[k] : -1;
-                out_bytes[(obase + s) * S + a] = real;
-                rv[k] -= c;
-                zero[k] = rv[k] == 0;
+            const i64 real = c < rl[k] ? c : rl[k];
+            rl[k] -= real;
+            rv[k] -= c;
+            if (lane + 64 * k < S) {
+                stg[off + 64 * k] = real > 0 ? mr[k] : -1;
+                byt[off + 64 * k] = real;
             }
+            zero[k] = rv[k] == 0;
+            Z[k] = ballot(zero[k]);
         }
-        if (lane == 0) wsC[obase + s] = c;
+        if (lane == 0) cw[s] = c;
         ++s;
+        off += S;
         Lrem -= c;
         if (Lrem == 0) break;
 
-        const u64 z0 = __ballot(zero[0]);
-        const u64 z1 = NR == 2 ? __ballot(zero[NR - 1]) : 0;
-        // unmatch every exhausted cell: column side drops the row from its support
+        int nz = 0;
 #pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            const int m = mc[k];
-            if (m >= 0 && (((m < 64 ? z0 : z1) >> (m & 63)) & 1)) {
-                if (m < 64) cmLo[k] &= ~(1ull << m);
-                else cmHi[k] &= ~(1ull << (m - 64));
-                mc[k] = -1;
+        for (int w = 0; w < NR; ++w) nz += __builtin_popcountll(Z[w]);
+        bool done = false;
+        if (nz == 1) {
+            // ---- fast path: one exhausted cell (r0, f); f is the only unmatched column
+            const int r0 = lowest(Z);
+            const int f = mr_of(r0);
+            u64 cmf[NR];
+            col_mask(f, cmf);
+            const u64 bit0 = 1ull << (r0 & 63);
+#pragma unroll
+            for (int w = 0; w < NR; ++w)
+                if ((r0 >> 6) == w) cmf[w] &= ~bit0;
+            // write the cleared support mask back to column f
+#pragma unroll
+            for (int k = 0; k < NR; ++k)
+#pragma unroll
+                for (int w = 0; w < NR; ++w)
+                    if ((f >> 6) == k && (r0 >> 6) == w) {
+                        cm[k][w] = lid[k] == f ? cmf[w] : cm[k][w];
+                    }
+            set_mr(r0, -1);
+            u64 F1[NR], N1[NR], F2[NR];
+#pragma unroll
+            for (int w = 0; w < NR; ++w) F1[w] = (r0 >> 6) == w ? bit0 : 0;
+            expand(F1, N1);
+            rows_matched_into(N1, F2);
+            u64 c2[NR];
+#pragma unroll
+            for (int w = 0; w < NR; ++w) c2[w] = cmf[w] & F2[w];
+            if (any(c2)) {
+                const int a1 = lowest(c2);
+                const int d1 = mr_of(a1);
+                set_mr(a1, f);
+                set_mr(r0, d1);
+                done = true;
+            } else if (any(N1)) {
+                u64 N2[NR], F3[NR], c3[NR];
+                expand(F2, N2);
+#pragma unroll
+                for (int w = 0; w < NR; ++w) N2[w] &= ~N1[w];
+                rows_matched_into(N2, F3);
+#pragma unroll
+                for (int w = 0; w < NR; ++w) c3[w] = cmf[w] & F3[w];
+                if (any(c3)) {
+                    const int a2 = lowest(c3);
+                    const int d2 = mr_of(a2);
+                    u64 cd[NR];
+                    col_mask(d2, cd);
+#pragma unroll
+                    for (int w = 0; w < NR; ++w) cd[w] &= F2[w];
+                    const int a1 = lowest(cd);
+                    const int d1 = mr_of(a1);
+                    set_mr(a2, f);
+                    set_mr(a1, d2);
+                    set_mr(r0, d1);
+                    done = true;
+                }
             }
-            if (zero[k]) mr[k] = -1;
+            if (!done) {
+                // deeper than three levels: let the general search redo it
+#pragma unroll
+                for (int w = 0; w < NR; ++w)
+                    if ((f >> 6) == w) FREEC[w] |= 1ull << (f & 63);
+                if (!augment(r0)) { status = -3; break; }
+            }
+        } else {
+            // ---- general path: unmatch every exhausted cell first, then re-augment in order
+            u64 z[NR];
+#pragma unroll
+            for (int w = 0; w < NR; ++w) z[w] = Z[w];
+            while (any(z)) {
+                const int a = lowest(z);
+                const int d = mr_of(a);
+                const u64 bit = 1ull << (a & 63);
+                const bool here = lane == (d & 63);
+#pragma unroll
+                for (int k = 0; k < NR; ++k) {
+                    if ((d >> 6) == k) {
+#pragma unroll
+                        for (int w = 0; w < NR; ++w)
+                            if ((a >> 6) == w) cm[k][w] = here ? cm[k][w] & ~bit : cm[k][w];
+                        FREEC[k] |= 1ull << (d & 63);
+                    }
+                }
+#pragma unroll
+                for (int w = 0; w < NR; ++w)
+                    if ((a >> 6) == w) z[w] &= ~bit;
+            }
+#pragma unroll
+            for (int k = 0; k < NR; ++k) mr[k] = zero[k] ? -1 : mr[k];
+            bool ok = true;
+#pragma unroll
+            for (int w = 0; w < NR; ++w)
+                for (u64 zz = Z[w]; zz && ok; zz &= zz - 1) ok = augment(64 * w + __builtin_ctzll(zz));
+            if (!ok) { status = -3; break; }
         }
-        bool ok = true;
-        for (u64 z = z0; z && ok; z &= z - 1) ok = augment(__builtin_ctzll(z));
-        if (NR == 2)
-            for (u64 z = z1; z && ok; z &= z - 1) ok = augment(64 + __builtin_ctzll(z));
-        if (!ok) { status = -3; break; }
         sync_matched();
     }
     if (lane == 0) out_num[b] = status < 0 ? status : s;
