@@ -42,6 +42,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "k1_rebalance.hpp"
 
 namespace fastk {
@@ -68,29 +70,41 @@ __device__ __forceinline__ u64 uniform64(u64 x) {
            (u64)(u32)__builtin_amdgcn_readfirstlane((u32)x);
 }
 
-template <int CTRL>
-__device__ __forceinline__ u32 dpp_min(u32 v) {
-    const u32 o = __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
-    return o < v ? o : v;
-}
-// min over the 64 lanes, result wave-uniform
+// min over the 64 lanes (all lanes must be active), result wave-uniform
 __device__ __forceinline__ u32 wave_min_u32(u32 v) {
-    v = dpp_min<0xB1>(v);    // quad_perm [1,0,3,2]
-    v = dpp_min<0x4E>(v);    // quad_perm [2,3,0,1]
-    v = dpp_min<0x141>(v);   // row_half_mirror
-    v = dpp_min<0x140>(v);   // row_mirror
-    const u32 a = rdl(v, 0), b = rdl(v, 16), c = rdl(v, 32), d = rdl(v, 48);
-    const u32 ab = a < b ? a : b, cd = c < d ? c : d;
-    return ab < cd ? ab : cd;
+    asm volatile(
+        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(v));
+    return rdl(v, 63);
 }
-// 64-bit minimum as two 32-bit passes: high words first, then the low words of
-// the lanes that hold the smallest high word
 __device__ __forceinline__ u64 wave_min_u64(u64 x) {
     const u32 hi = (u32)(x >> 32);
+    const u64 small = ballot(hi == 0);
+    if (small) {      // some value fits 32 bits: the minimum is among those
+        const u32 lo = hi == 0 ? (u32)x : 0xFFFFFFFFu;
+        return wave_min_u32(lo);
+    }
     const u32 mhi = wave_min_u32(hi);
     const u32 lo = hi == mhi ? (u32)x : 0xFFFFFFFFu;
     const u32 mlo = wave_min_u32(lo);
     return ((u64)mhi << 32) | mlo;
+}
+// v[lane] = val for one lane; val and lane are wave-uniform
+__device__ __forceinline__ void wrlane(u32& v, u32 val, int lane) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0"
+                 : "+v"(v) : "s"(val), "s"(lane));
+}
+__device__ __forceinline__ void wrlane64(u64& v, u64 val, int lane) {
+    u32 lo = (u32)v, hi = (u32)(v >> 32);
+    asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\tv_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
+                 : "+v"(lo), "+v"(hi) : "s"((u32)val), "s"((u32)(val >> 32)), "s"(lane));
+    v = ((u64)hi << 32) | lo;
 }
 __device__ __forceinline__ i64 wave_max_i64(i64 v) {
 #pragma unroll
@@ -123,7 +137,6 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     const int b = blockIdx.x;
     const int lane = threadIdx.x;
 
-    // a negative entry anywhere in the matrix: no plan
     {
         int bad = 0;
         for (int a = lane; a < S; a += 64) bad |= (int)wsPart[((size_t)b * S + a) * K1_PART + 2];
@@ -132,12 +145,10 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             return;
         }
     }
-    // ---- load Q (per-lane bytes of every server pair, diagonal zero)
     const i64* Qg = wsQ + (size_t)b * S * S;
     for (int e = lane; e < S * S; e += 64) R[e] = (u64)Qg[e];
     __syncthreads();
 
-    // ---- row / column sums, L = heaviest line (Section 4.4)
     i64 rsum[NR], csum[NR];
 #pragma unroll
     for (int k = 0; k < NR; ++k) {
@@ -162,7 +173,6 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         return;
     }
 
-    // ---- embedding: diagonal first, then row deficits poured into column deficits
     i64 diag[NR], PR[NR], ER[NR];
     {
         i64 dr[NR], dc[NR];
@@ -227,6 +237,13 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         }
     }
 
+    int lid[NR];
+    u32 rowbase[NR];
+#pragma unroll
+    for (int k = 0; k < NR; ++k) {
+        lid[k] = lane + 64 * k;
+        rowbase[k] = lane + 64 * k < S ? (u32)(lane + 64 * k) * (u32)S : 0u;
+    }
     int mr[NR], loaded[NR];
     i64 rv[NR], rl[NR];
     u64 vfl[NR];
@@ -375,34 +392,37 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         return true;
     };
 
+    // Make rv / rl describe the cell each row is matched to now.  Loads are
+    // issued for every row (cheap, no exec juggling) and kept only where the
+    // match changed; the old cell's residual is written back where it is non-zero.
     auto sync_matched = [&]() {
-        bool needv[NR];
+        u64 x[NR];
+        bool ch[NR];
 #pragma unroll
         for (int k = 0; k < NR; ++k) {
-            const int a = lane + 64 * k;
-            needv[k] = false;
-            if (mr[k] != loaded[k]) {
-                if (rv[k] > 0) R[(size_t)a * S + loaded[k]] = (u64)rv[k] | vfl[k];
-                const u64 x = R[(size_t)a * S + mr[k]];
-                vfl[k] = x & VFLAG;
-                rv[k] = (i64)(x & ~VFLAG);
-                rl[k] = rv[k];
-                loaded[k] = mr[k];
-                needv[k] = vfl[k] != 0;
-            }
+            ch[k] = mr[k] != loaded[k];
+            if (ch[k] && rv[k] > 0) R[rowbase[k] + (u32)loaded[k]] = (u64)rv[k] | vfl[k];
+            x[k] = R[rowbase[k] + (u32)max(mr[k], 0)];
         }
-        bool anyv = false;
+        u64 anyv = 0;
 #pragma unroll
-        for (int k = 0; k < NR; ++k) anyv = anyv || ballot(needv[k]) != 0;
+        for (int k = 0; k < NR; ++k) {
+            const u64 val = x[k] & ~VFLAG;
+            const u64 fl = x[k] & VFLAG;
+            rv[k] = ch[k] ? (i64)val : rv[k];
+            rl[k] = ch[k] ? (i64)val : rl[k];
+            anyv |= ballot(ch[k] && fl != 0);
+            vfl[k] = ch[k] ? fl : vfl[k];
+            loaded[k] = mr[k];
+        }
         if (anyv) {
 #pragma unroll
             for (int k = 0; k < NR; ++k) {
-                if (needv[k]) {
-                    const int a = lane + 64 * k;
+                if (ch[k] && vfl[k] != 0) {
                     const int d = mr[k];
                     const i64 l = max(PR[k], PC[d]);
                     const i64 h = min(ER[k], EC[d]);
-                    const i64 av = (h > l ? h - l : 0) + (d == a ? diag[k] : 0);
+                    const i64 av = (h > l ? h - l : 0) + (d == lid[k] ? diag[k] : 0);
                     rl[k] = rv[k] > av ? rv[k] - av : 0;
                 }
             }
@@ -426,18 +446,16 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     i64* cw = wsC + (size_t)b * max_stages;
     i64 Lrem = L;
     int s = 0;
-    u32 off = lane;
-    int lid[NR];
-    u32 rowbase[NR];
-#pragma unroll
-    for (int k = 0; k < NR; ++k) {
-        lid[k] = lane + 64 * k;
-        rowbase[k] = (u32)(lane + 64 * k) * (u32)S;
-    }
+    int32_t* srow = stg;
+    i64* brow = byt;
     // mr of a uniform row
     auto mr_of = [&](int a) -> int {
-        if constexpr (NR == 2) return (int)rdl((u32)((a & 64) ? mr[1] : mr[0]), a & 63);
-        else return (int)rdl((u32)mr[0], a);
+        if constexpr (NR == 2) {
+            const int x0 = (int)rdl((u32)mr[0], a & 63), x1 = (int)rdl((u32)mr[1], a & 63);
+            return (a & 64) ? x1 : x0;
+        } else {
+            return (int)rdl((u32)mr[0], a);
+        }
     };
     auto set_mr = [&](int a, int d) {
 #pragma unroll
@@ -477,16 +495,17 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             const i64 real = c < rl[k] ? c : rl[k];
             rl[k] -= real;
             rv[k] -= c;
-            if (lane + 64 * k < S) {
-                stg[off + 64 * k] = real > 0 ? mr[k] : -1;
-                byt[off + 64 * k] = real;
+            if (lid[k] < S) {
+                srow[lid[k]] = real > 0 ? mr[k] : -1;
+                brow[lid[k]] = real;
             }
             zero[k] = rv[k] == 0;
             Z[k] = ballot(zero[k]);
         }
         if (lane == 0) cw[s] = c;
         ++s;
-        off += S;
+        srow += S;
+        brow += S;
         Lrem -= c;
         if (Lrem == 0) break;
 
@@ -495,29 +514,41 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         for (int w = 0; w < NR; ++w) nz += __builtin_popcountll(Z[w]);
         bool done = false;
         if (nz == 1) {
-            // ---- fast path: one exhausted cell (r0, f); f is the only unmatched column
+            // ---- fast path: one exhausted cell (r0, f); f is the only unmatched column.
+            // Row r0 keeps naming f as its column until the flip; f is not adjacent to
+            // r0 any more, so r0 cannot enter a frontier through it.
             const int r0 = lowest(Z);
             const int f = mr_of(r0);
-            u64 cmf[NR];
-            col_mask(f, cmf);
             const u64 bit0 = 1ull << (r0 & 63);
+            u64 cmf[NR], N1[NR], F2[NR];
+            // KF = column slot of f, WR = mask word of r0 (compile-time in each branch)
+            auto level1 = [&](auto KFc, auto WRc) {
+                constexpr int KF = decltype(KFc)::value, WR = decltype(WRc)::value;
 #pragma unroll
-            for (int w = 0; w < NR; ++w)
-                if ((r0 >> 6) == w) cmf[w] &= ~bit0;
-            // write the cleared support mask back to column f
+                for (int w = 0; w < NR; ++w) cmf[w] = rdl64(cm[KF][w], f & 63);
+                cmf[WR] &= ~bit0;
+                wrlane64(cm[KF][WR], cmf[WR], f & 63);
 #pragma unroll
-            for (int k = 0; k < NR; ++k)
+                for (int k = 0; k < NR; ++k) N1[k] = ballot((cm[k][WR] & bit0) != 0);
+            };
+            if constexpr (NR == 2) {
+                const int sel = ((f >> 6) << 1) | (r0 >> 6);
+                if (sel == 0) level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+                else if (sel == 1) level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
+                else if (sel == 2) level1(std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
+                else level1(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
+            } else {
+                level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+            }
+            // every row is matched here (r0 nominally), so no "unmatched" test is needed
 #pragma unroll
-                for (int w = 0; w < NR; ++w)
-                    if ((f >> 6) == k && (r0 >> 6) == w) {
-                        cm[k][w] = lid[k] == f ? cmf[w] : cm[k][w];
-                    }
-            set_mr(r0, -1);
-            u64 F1[NR], N1[NR], F2[NR];
-#pragma unroll
-            for (int w = 0; w < NR; ++w) F1[w] = (r0 >> 6) == w ? bit0 : 0;
-            expand(F1, N1);
-            rows_matched_into(N1, F2);
+            for (int k = 0; k < NR; ++k) {
+                const int m = mr[k];
+                u64 t;
+                if constexpr (NR == 2) t = (m & 64) ? (N1[1] >> (m & 63)) : (N1[0] >> (m & 63));
+                else t = N1[0] >> (m & 63);
+                F2[k] = ballot((t & 1) != 0);
+            }
             u64 c2[NR];
 #pragma unroll
             for (int w = 0; w < NR; ++w) c2[w] = cmf[w] & F2[w];
@@ -528,6 +559,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 set_mr(r0, d1);
                 done = true;
             } else if (any(N1)) {
+                set_mr(r0, -1);
                 u64 N2[NR], F3[NR], c3[NR];
                 expand(F2, N2);
 #pragma unroll
@@ -552,6 +584,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             }
             if (!done) {
                 // deeper than three levels: let the general search redo it
+                set_mr(r0, -1);
 #pragma unroll
                 for (int w = 0; w < NR; ++w)
                     if ((f >> 6) == w) FREEC[w] |= 1ull << (f & 63);
