@@ -317,9 +317,14 @@ int decompose(int S, const i64* Q, const i64* A, int cap, int32_t* stages, i64* 
 //   stage; with sizes sorted ascending l_0 <= l_1 <= ... the exposed part
 //   sum_{i>=1} max(0, (G-1) l_{i-1}/B_up - l_i/B_out) is added (t_exc).
 //   t_opt = max(max row sum, max column sum of T) / (G * B_out)   (Theorem 1).
+//   wake-up delay (Section 5.4: every transfer step costs a fixed link wake-up
+//   delay plus size/bandwidth): `delay` seconds are added once per executed step;
+//   the steps are the balance (if anything is handed off), the intra-server
+//   portion (if any), each of the K stages, and the last redistribution (if G > 1
+//   and K > 0).  The paper gives no value for it; 0 reproduces the Appendix.
 // out4 = {T_pred, t0, t2, t_opt}; extra3 (optional) = {t1, t3, t_exc}.
 // ---------------------------------------------------------------------------
-void cost(int S, int G, double bw_up, double bw_out, const i64* T, const i64* X,
+void cost(int S, int G, double bw_up, double bw_out, double delay, const i64* T, const i64* X,
           const i64* intra_out, const i64* intra_in, int K, const i64* bytes, double* out4,
           double* extra3) {
     const int N = S * G;
@@ -372,11 +377,57 @@ void cost(int S, int G, double bw_up, double bw_out, const i64* T, const i64* X,
     tp = tp + t2;
     tp = tp + t3;
     tp = tp + texc;
+    const int steps = (bal > 0 ? 1 : 0) + (intra > 0 ? 1 : 0) + (K > 0 ? K : 0) +
+                      ((i64)(G - 1) * cmax > 0 ? 1 : 0);
+    tp = tp + delay * (double)steps;
     out4[0] = tp;
     out4[1] = t0;
     out4[2] = t2;
     out4[3] = (double)big / ((double)G * bw_out);
     if (extra3) { extra3[0] = t1; extra3[1] = t3; extra3[2] = texc; }
+}
+
+// ---------------------------------------------------------------------------
+// SpreadOut baseline (Section 4.2 "SpreadOut: one-to-one but not optimal";
+// Section 5.4 compares FAST with it in simulation): stage i pairs endpoint s with
+// endpoint (s+i) mod n for i = 1..n-1, every stage lasts as long as its largest
+// transfer, so the completion time is the sum over shifted diagonals of the
+// largest entry's transfer time (plus the wake-up delay per non-empty stage).
+//   out2[0]: SpreadOut over the N GPUs on the raw matrix, a pair inside a server
+//            moving at B_up and a pair across servers at B_out;
+//   out2[1]: SpreadOut over the S servers on the balanced per-lane matrix Q (the
+//            comparison of Fig. 7: same balancing as FAST, shifted diagonals
+//            instead of Birkhoff stages).
+// Returns -1 if an off-diagonal entry is negative.
+// ---------------------------------------------------------------------------
+int spreadout(int S, int G, double bw_up, double bw_out, double delay, const i64* traffic,
+              double* out2) {
+    const int N = S * G;
+    std::vector<i64> T((size_t)S * S), Q((size_t)S * S), io(N), ii(N);
+    if (aggregate(S, G, traffic, T.data(), io.data(), ii.data()) != 0) return -1;
+    double tg = 0.0;
+    for (int i = 1; i < N; ++i) {
+        i64 up = 0, out = 0;
+        for (int g = 0; g < N; ++g) {
+            const int h = (g + i) % N;
+            const i64 v = at(traffic, N, g, h);
+            if (g / G == h / G) up = std::max(up, v); else out = std::max(out, v);
+        }
+        if (up > 0 || out > 0) {
+            const double a = (double)up / bw_up, b = (double)out / bw_out;
+            tg = tg + (delay + (a > b ? a : b));
+        }
+    }
+    collapse(S, G, T.data(), Q.data());
+    double ts = 0.0;
+    for (int i = 1; i < S; ++i) {
+        i64 m = 0;
+        for (int a = 0; a < S; ++a) m = std::max(m, at(Q.data(), S, a, (a + i) % S));
+        if (m > 0) ts = ts + (delay + (double)m / bw_out);
+    }
+    out2[0] = tg;
+    out2[1] = ts;
+    return 0;
 }
 
 }  // namespace
@@ -409,16 +460,22 @@ int oracle_decompose(int S, const int64_t* Q, const int64_t* A, int cap, int32_t
     return decompose(S, Q, A, cap, stages, bytes);
 }
 
-void oracle_cost(int S, int G, double bw_up, double bw_out, const int64_t* T, const int64_t* X,
-                 const int64_t* intra_out, const int64_t* intra_in, int K, const int64_t* bytes,
-                 double* out4, double* extra3) {
-    cost(S, G, bw_up, bw_out, T, X, intra_out, intra_in, K, bytes, out4, extra3);
+void oracle_cost(int S, int G, double bw_up, double bw_out, double delay, const int64_t* T,
+                 const int64_t* X, const int64_t* intra_out, const int64_t* intra_in, int K,
+                 const int64_t* bytes, double* out4, double* extra3) {
+    cost(S, G, bw_up, bw_out, delay, T, X, intra_out, intra_in, K, bytes, out4, extra3);
+}
+
+int oracle_spreadout(int S, int G, double bw_up, double bw_out, double delay,
+                     const int64_t* traffic, double* out2) {
+    return spreadout(S, G, bw_up, bw_out, delay, traffic, out2);
 }
 
 // Whole path for one matrix.  stages/bytes hold `cap` stage rows of S entries;
 // rows >= K are left untouched.  *num_stages = K >= 0, -1 (negative entry),
 // -2 (cap exceeded), -3 (internal).  Q_out / A_out (S*S each) may be NULL.
-int oracle_synthesize(int S, int G, double bw_up, double bw_out, const int64_t* traffic,
+int oracle_synthesize(int S, int G, double bw_up, double bw_out, double delay,
+                      const int64_t* traffic,
                       int64_t* X, int32_t* stages, int64_t* bytes, int cap, int32_t* num_stages,
                       double* out4, double* extra3, int64_t* Q_out, int64_t* A_out) {
     const int N = S * G;
@@ -435,7 +492,7 @@ int oracle_synthesize(int S, int G, double bw_up, double bw_out, const int64_t* 
     if (Q_out) std::memcpy(Q_out, Q.data(), sizeof(i64) * S * S);
     if (A_out) std::memcpy(A_out, A.data(), sizeof(i64) * S * S);
     if (K < 0) return 0;
-    cost(S, G, bw_up, bw_out, T.data(), X, io.data(), ii.data(), K, bytes, out4, extra3);
+    cost(S, G, bw_up, bw_out, delay, T.data(), X, io.data(), ii.data(), K, bytes, out4, extra3);
     return 0;
 }
 

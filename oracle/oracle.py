@@ -50,12 +50,16 @@ def lib():
         L.oracle_decompose.argtypes = [ctypes.c_int, _i64p, _i64p, ctypes.c_int, _i32p, _i64p]
         L.oracle_decompose.restype = ctypes.c_int
         L.oracle_cost.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double,
-                                  _i64p, _i64p, _i64p, _i64p, ctypes.c_int, _i64p, _f64p, _f64p]
+                                  ctypes.c_double, _i64p, _i64p, _i64p, _i64p, ctypes.c_int,
+                                  _i64p, _f64p, _f64p]
         L.oracle_cost.restype = None
         L.oracle_synthesize.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double,
-                                        ctypes.c_double, _i64p, _i64p, _i32p, _i64p, ctypes.c_int,
-                                        _i32p, _f64p, _f64p, _i64p, _i64p]
+                                        ctypes.c_double, ctypes.c_double, _i64p, _i64p, _i32p,
+                                        _i64p, ctypes.c_int, _i32p, _f64p, _f64p, _i64p, _i64p]
         L.oracle_synthesize.restype = ctypes.c_int
+        L.oracle_spreadout.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double,
+                                       ctypes.c_double, _i64p, _f64p]
+        L.oracle_spreadout.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -136,7 +140,7 @@ def decompose(Q, A, cap=None):
     return K, st[:K].copy(), by[:K].copy()
 
 
-def cost(S, G, bw_up, bw_out, T, X, io, ii, stage_bytes):
+def cost(S, G, bw_up, bw_out, T, X, io, ii, stage_bytes, delay=0.0):
     """-> (out4 = [T_pred, t0, t2, t_opt], extra3 = [t1, t3, t_exc])"""
     T = _c64(T)
     X = _c64(X)
@@ -147,7 +151,7 @@ def cost(S, G, bw_up, bw_out, T, X, io, ii, stage_bytes):
     by = _c64(by if K else np.zeros((1, S), np.int64))
     out4 = np.zeros(4, np.float64)
     ex = np.zeros(3, np.float64)
-    lib().oracle_cost(S, G, bw_up, bw_out, _p64(T), _p64(X), _p64(io), _p64(ii), K, _p64(by),
+    lib().oracle_cost(S, G, bw_up, bw_out, delay, _p64(T), _p64(X), _p64(io), _p64(ii), K, _p64(by),
                       _pf(out4), _pf(ex))
     return out4, ex
 
@@ -157,7 +161,7 @@ class Plan:
     __slots__ = ("status", "K", "X", "stages", "stage_bytes", "time4", "extra3", "Q", "A")
 
 
-def synthesize(S, G, bw_up, bw_out, traffic, cap=None):
+def synthesize(S, G, bw_up, bw_out, traffic, cap=None, delay=0.0):
     N = S * G
     traffic = _c64(traffic).reshape(N, N)
     cap = S * S if cap is None else cap
@@ -169,7 +173,7 @@ def synthesize(S, G, bw_up, bw_out, traffic, cap=None):
     ex = np.zeros(3, np.float64)
     Q = np.zeros((S, S), np.int64)
     A = np.zeros((S, S), np.int64)
-    lib().oracle_synthesize(S, G, bw_up, bw_out, _p64(traffic), _p64(X), _p32(st), _p64(by), cap,
+    lib().oracle_synthesize(S, G, bw_up, bw_out, delay, _p64(traffic), _p64(X), _p32(st), _p64(by), cap,
                             _p32(ns), _pf(out4), _pf(ex), _p64(Q), _p64(A))
     p = Plan()
     p.status = int(ns[0])
@@ -182,3 +186,12 @@ def synthesize(S, G, bw_up, bw_out, traffic, cap=None):
     p.Q = Q
     p.A = A
     return p
+
+
+def spreadout(S, G, bw_up, bw_out, traffic, delay=0.0):
+    """-> (status, [t_gpu_level, t_server_level])"""
+    N = S * G
+    traffic = _c64(traffic).reshape(N, N)
+    out2 = np.zeros(2, np.float64)
+    st = lib().oracle_spreadout(S, G, bw_up, bw_out, delay, _p64(traffic), _pf(out2))
+    return st, out2
