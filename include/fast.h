@@ -113,6 +113,36 @@ int fast_synthesize_batched(fast_plan_t *plan, int B,
                             hipStream_t stream);
 
 /*
+ * Link wake-up delay of the completion-time model (Section 5.4: every transfer step
+ * costs a fixed wake-up delay plus size / bandwidth).  `seconds` >= 0 is added to T_pred
+ * once per executed step - the balance (if anything is handed off), the intra-server
+ * portion (if any), each stage, the last redistribution (if G > 1 and there is a stage)
+ * - and to every non-empty SpreadOut stage.  The paper gives no value; the default 0
+ * reproduces the Appendix.  FAST_ERR_INVALID_ARG if plan is NULL or seconds is negative
+ * or not finite.
+ */
+int fast_plan_set_wakeup_delay(fast_plan_t *plan, double seconds);
+
+/*
+ * SpreadOut baseline (Section 4.2 "SpreadOut: one-to-one but not optimal"; the
+ * comparison schedule of the Section 5.4 simulation): stage i pairs endpoint s with
+ * endpoint (s+i) mod n, every stage lasts as long as its largest transfer.  For each of
+ * the B matrices (device, [B][N][N], as for fast_synthesize_batched) writes to
+ *   out_spreadout_time  device, [B][2] seconds:
+ *     [0] SpreadOut over the N GPUs on the raw matrix: sum over i = 1..N-1 of the
+ *         non-empty stages' (delay + max over g of traffic[g][(g+i) mod N] / bandwidth of
+ *         that pair), a pair inside a server moving at link_bw_up, across servers at
+ *         link_bw_out;
+ *     [1] SpreadOut over the S servers on the balanced per-lane matrix Q = ceil(T/G):
+ *         sum over i = 1..S-1 of (delay + max over a of Q[a][(a+i) mod S] / link_bw_out);
+ *     both are -1 for a matrix with a negative off-diagonal entry.
+ * Enqueued on `stream`, asynchronous, same ownership and ordering rules as
+ * fast_synthesize_batched; uses its own part of the plan's workspace.
+ */
+int fast_spreadout_batched(fast_plan_t *plan, int B, const int64_t *traffic,
+                           double *out_spreadout_time, hipStream_t stream);
+
+/*
  * Per-kernel timing for measurement.  fast_plan_set_timing(plan, 1) starts a new
  * recording (dropping any earlier one): each following fast_synthesize_batched call,
  * up to FAST_MAX_TIMED_CALLS of them, records HIP events on its stream around its

@@ -22,6 +22,7 @@ FAST_STATUS_STAGE_OVERFLOW = -2
 FAST_STATUS_INTERNAL = -3
 
 EXPORTS = ("fast_plan_create", "fast_plan_max_stages", "fast_synthesize_batched",
+           "fast_plan_set_wakeup_delay", "fast_spreadout_batched",
            "fast_plan_set_timing", "fast_plan_timed_calls", "fast_plan_kernel_ms",
            "fast_plan_destroy")
 
@@ -51,6 +52,10 @@ def lib():
         L.fast_plan_max_stages.restype = ctypes.c_int
         L.fast_synthesize_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp]
         L.fast_synthesize_batched.restype = ctypes.c_int
+        L.fast_plan_set_wakeup_delay.argtypes = [vp, ctypes.c_double]
+        L.fast_plan_set_wakeup_delay.restype = ctypes.c_int
+        L.fast_spreadout_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp]
+        L.fast_spreadout_batched.restype = ctypes.c_int
         L.fast_plan_set_timing.argtypes = [vp, ctypes.c_int]
         L.fast_plan_set_timing.restype = ctypes.c_int
         L.fast_plan_timed_calls.argtypes = [vp]
@@ -85,6 +90,19 @@ def fast_synthesize_batched(plan, B, traffic, out_rebalance, out_stages, out_sta
                                        out_stage_bytes, out_num_stages, out_predicted_time, stream)
     if rc != FAST_OK:
         raise FastError("fast_synthesize_batched", rc)
+
+
+def fast_plan_set_wakeup_delay(plan, seconds):
+    rc = lib().fast_plan_set_wakeup_delay(plan, float(seconds))
+    if rc != FAST_OK:
+        raise FastError("fast_plan_set_wakeup_delay", rc)
+
+
+def fast_spreadout_batched(plan, B, traffic, out_spreadout_time, stream):
+    """Raw call: buffer arguments are device addresses (int), stream a hipStream_t (int)."""
+    rc = lib().fast_spreadout_batched(plan, int(B), traffic, out_spreadout_time, stream)
+    if rc != FAST_OK:
+        raise FastError("fast_spreadout_batched", rc)
 
 
 def fast_plan_set_timing(plan, enable):
@@ -153,6 +171,25 @@ class Synthesizer:
                                     out.stages.data_ptr(), out.stage_bytes.data_ptr(),
                                     out.num_stages.data_ptr(), out.predicted_time.data_ptr(),
                                     stream)
+        return out
+
+    def set_wakeup_delay(self, seconds):
+        fast_plan_set_wakeup_delay(self.plan, seconds)
+
+    def spreadout(self, traffic, out=None):
+        """SpreadOut baseline times -> float64 tensor [B, 2] (GPU level, server level)."""
+        import torch
+        N = self.S * self.G
+        if traffic.dtype != torch.int64 or traffic.dim() != 3 or tuple(traffic.shape[1:]) != (N, N):
+            raise ValueError(f"traffic must be int64 [B, {N}, {N}]")
+        if not traffic.is_cuda or traffic.device != self.device or not traffic.is_contiguous():
+            raise ValueError("traffic must be a contiguous tensor on the plan's device")
+        B = traffic.shape[0]
+        if out is None:
+            out = torch.empty((B, 2), dtype=torch.float64, device=self.device)
+        with torch.cuda.device(self.device):
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+            fast_spreadout_batched(self.plan, B, traffic.data_ptr(), out.data_ptr(), stream)
         return out
 
     def set_timing(self, enable):

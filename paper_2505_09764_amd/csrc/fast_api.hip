@@ -11,12 +11,14 @@
 #include "k1_rebalance.hpp"
 #include "k2_birkhoff.hpp"
 #include "k3_cost.hpp"
+#include "k4_spreadout.hpp"
 
 using fastk::i64;
 
 struct fast_plan {
     int S, G;
     double bw_up, bw_out;
+    double delay;  // link wake-up delay per executed step, seconds
     int device;
     int max_stages;
     // device workspace for `cap_B` matrices
@@ -25,6 +27,11 @@ struct fast_plan {
     i64* wsQ;      // [B][S][S]  per-lane server-level matrix
     i64* wsPart;   // [B][S][K1_PART]
     i64* wsC;      // [B][max_stages] stage weights
+    // workspace of the SpreadOut baseline for `spo_cap_B` matrices
+    int spo_cap_B;
+    fastk::u64* spoDiag;   // [B][2][N] per-diagonal maxima
+    i64* spoT;             // [B][S][S]
+    int* spoNeg;           // [B][chunks]
     // timing: four events per recorded call
     int timing;
     int n_timed;
@@ -37,6 +44,49 @@ void free_workspace(fast_plan* p) {
     if (p->wsT) (void)hipFree(p->wsT);
     p->wsT = p->wsQ = p->wsPart = p->wsC = nullptr;
     p->cap_B = 0;
+}
+
+void free_spo_workspace(fast_plan* p) {
+    if (p->spoDiag) (void)hipFree(p->spoDiag);
+    p->spoDiag = nullptr;
+    p->spoT = nullptr;
+    p->spoNeg = nullptr;
+    p->spo_cap_B = 0;
+}
+
+int grow_spo_workspace(fast_plan* p, int B) {
+    if (B <= p->spo_cap_B) return FAST_OK;
+    free_spo_workspace(p);
+    const size_t S = p->S, N = (size_t)p->S * p->G;
+    const size_t chunks = (S + fastk::spo_chunk_servers(p->S, p->G) - 1) /
+                          fastk::spo_chunk_servers(p->S, p->G);
+    const size_t nDiag = (size_t)B * 2 * N, nT = (size_t)B * S * S, nNeg = (size_t)B * chunks;
+    unsigned char* base = nullptr;
+    if (hipMalloc(&base, (nDiag + nT) * sizeof(i64) + nNeg * sizeof(int)) != hipSuccess) {
+        (void)hipGetLastError();
+        return FAST_ERR_OOM;
+    }
+    p->spoDiag = reinterpret_cast<fastk::u64*>(base);
+    p->spoT = reinterpret_cast<i64*>(p->spoDiag + nDiag);
+    p->spoNeg = reinterpret_cast<int*>(p->spoT + nT);
+    p->spo_cap_B = B;
+    return FAST_OK;
+}
+
+template <int G>
+void launch_spo_scan(const fast_plan* p, int B, const i64* traffic, int CS, int chunks,
+                     hipStream_t stream) {
+    const dim3 grid(chunks, B), block(fastk::SPO_THREADS);
+    const size_t lds = fastk::spo_scan_lds_bytes(p->S, G);
+    if constexpr (G % 2 == 0) {
+        if (reinterpret_cast<uintptr_t>(traffic) % 16 == 0) {
+            hipLaunchKernelGGL((fastk::spo_scan<G, true>), grid, block, lds, stream, traffic,
+                               p->spoDiag, p->spoT, p->spoNeg, p->S, CS);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((fastk::spo_scan<G, false>), grid, block, lds, stream, traffic, p->spoDiag,
+                       p->spoT, p->spoNeg, p->S, CS);
 }
 
 int grow_workspace(fast_plan* p, int B) {
@@ -106,8 +156,13 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     p->bw_out = link_bw_out;
     p->device = dev;
     p->max_stages = S * S;
+    p->delay = 0.0;
     p->cap_B = 0;
     p->wsT = p->wsQ = p->wsPart = p->wsC = nullptr;
+    p->spo_cap_B = 0;
+    p->spoDiag = nullptr;
+    p->spoT = nullptr;
+    p->spoNeg = nullptr;
     p->timing = 0;
     p->n_timed = 0;
     p->ev = nullptr;
@@ -195,11 +250,52 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
     hipLaunchKernelGGL(fastk::k3_cost, dim3(B), dim3(fastk::K3_THREADS),
                        (size_t)sort_n * sizeof(i64), stream, p->wsT, p->wsPart, p->wsC,
                        out_num_stages, out_predicted_time, p->S, p->G, p->max_stages, p->bw_up,
-                       p->bw_out, sort_n);
+                       p->bw_out, p->delay, sort_n);
     if (ev) {
         (void)hipEventRecord(ev[3], stream);
         ++p->n_timed;
     }
+    if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
+    return FAST_OK;
+}
+
+int fast_plan_set_wakeup_delay(fast_plan_t* p, double seconds) {
+    if (!p || !std::isfinite(seconds) || seconds < 0.0) return FAST_ERR_INVALID_ARG;
+    p->delay = seconds;
+    return FAST_OK;
+}
+
+int fast_spreadout_batched(fast_plan_t* p, int B, const int64_t* traffic,
+                           double* out_spreadout_time, hipStream_t stream) {
+    if (!p || B < 0) return FAST_ERR_INVALID_ARG;
+    if (B == 0) return FAST_OK;
+    if (!traffic || !out_spreadout_time) return FAST_ERR_INVALID_ARG;
+    if (B > 65535) return FAST_ERR_UNSUPPORTED;
+    const int rc = grow_spo_workspace(p, B);
+    if (rc != FAST_OK) return rc;
+    const int N = p->S * p->G;
+    const int CS = fastk::spo_chunk_servers(p->S, p->G);
+    const int chunks = (p->S + CS - 1) / CS;
+    const size_t nDiag = (size_t)B * 2 * N;
+    // the per-diagonal maxima are merged with atomic max, so they start from zero
+    // (a fill kernel, not a memset node, so that the call can be captured in a graph)
+    hipLaunchKernelGGL(fastk::spo_zero, dim3((unsigned)((nDiag + 1023) / 1024 < 1024
+                                                           ? (nDiag + 1023) / 1024 : 1024)),
+                       dim3(256), 0, stream, p->spoDiag, nDiag);
+    const i64* tr = reinterpret_cast<const i64*>(traffic);
+    switch (p->G) {
+        case 1: launch_spo_scan<1>(p, B, tr, CS, chunks, stream); break;
+        case 2: launch_spo_scan<2>(p, B, tr, CS, chunks, stream); break;
+        case 3: launch_spo_scan<3>(p, B, tr, CS, chunks, stream); break;
+        case 4: launch_spo_scan<4>(p, B, tr, CS, chunks, stream); break;
+        case 5: launch_spo_scan<5>(p, B, tr, CS, chunks, stream); break;
+        case 6: launch_spo_scan<6>(p, B, tr, CS, chunks, stream); break;
+        case 7: launch_spo_scan<7>(p, B, tr, CS, chunks, stream); break;
+        default: launch_spo_scan<8>(p, B, tr, CS, chunks, stream); break;
+    }
+    hipLaunchKernelGGL(fastk::spo_finish, dim3(B), dim3(fastk::SPO_THREADS),
+                       (size_t)N * sizeof(double), stream, p->spoDiag, p->spoT, p->spoNeg,
+                       out_spreadout_time, p->S, p->G, chunks, p->bw_up, p->bw_out, p->delay);
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     return FAST_OK;
 }
@@ -231,6 +327,7 @@ int fast_plan_kernel_ms(fast_plan_t* p, int call, float* out_ms) {
 void fast_plan_destroy(fast_plan_t* p) {
     if (!p) return;
     free_workspace(p);
+    free_spo_workspace(p);
     if (p->ev) {
         for (int c = 0; c < FAST_MAX_TIMED_CALLS; ++c)
             for (int k = 0; k < 4; ++k)

@@ -12,9 +12,12 @@
 //   t_exc = exposed redistribution when B_up < (G-1) B_out: with the stage weights
 //           sorted ascending, sum_{i>=1} max(0, (G-1) l_{i-1}/B_up - l_i/B_out)
 //           (proof of Theorem 2, steps (i)-(iii)); otherwise 0
+//   delay = link wake-up delay, added once per executed step: the balance (if
+//           anything is handed off), the intra-server portion (if any), each
+//           stage, the last redistribution (if G > 1 and there is a stage)
 //   t_opt = max(max row sum, max column sum of T) / (G * B_out)
 // All reductions are exact int64; each term is one conversion and one division.
-// out[b] = { t0 + t1 + t2 + t3 + t_exc, t0, t2, t_opt }.
+// out[b] = { t0 + t1 + t2 + t3 + t_exc + delay * steps, t0, t2, t_opt }.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -45,7 +48,7 @@ __device__ __forceinline__ i64 block_reduce(i64 v, bool is_max, i64* scratch) {
 __global__ void __launch_bounds__(K3_THREADS)
 k3_cost(const i64* __restrict__ wsT, const i64* __restrict__ wsPart, const i64* __restrict__ wsC,
         const int32_t* __restrict__ out_num, double* __restrict__ out_time, int S, int G,
-        int max_stages, double bw_up, double bw_out, int sort_n) {
+        int max_stages, double bw_up, double bw_out, double delay, int sort_n) {
     extern __shared__ __align__(16) unsigned char k3_smem[];
     __shared__ i64 scratch[K3_THREADS / 64];
     const int b = blockIdx.x;
@@ -116,6 +119,9 @@ k3_cost(const i64* __restrict__ wsT, const i64* __restrict__ wsPart, const i64* 
         tp = tp + t2;
         tp = tp + t3;
         tp = tp + texc;
+        const int steps = (bal > 0 ? 1 : 0) + (intra > 0 ? 1 : 0) + K +
+                          ((i64)(G - 1) * cmax > 0 ? 1 : 0);
+        tp = __dadd_rn(tp, __dmul_rn(delay, (double)steps));   // no fused multiply-add
         out[0] = tp;
         out[1] = t0;
         out[2] = t2;

@@ -260,3 +260,77 @@ def test_plan_reuse_and_b0(torch_cuda):
     ms = syn.kernel_ms()
     assert len(ms) == 2 and all(len(m) == 3 and all(x > 0 for x in m) for m in ms)
     syn.close()
+
+
+# ----------------------------------------------------------------------------
+# SpreadOut baseline and wake-up delay
+# ----------------------------------------------------------------------------
+def run_spreadout(torch, S, G, bw_up, bw_out, traffic, delay=0.0):
+    from paper_2505_09764_amd.binding import Synthesizer
+    dev = torch.device("cuda:0")
+    t = traffic if isinstance(traffic, torch.Tensor) else torch.from_numpy(
+        np.ascontiguousarray(traffic, dtype=np.int64)).to(dev)
+    syn = Synthesizer(S, G, bw_up, bw_out, dev)
+    syn.set_wakeup_delay(delay)
+    out = syn.spreadout(t)
+    out2 = syn.spreadout(t)              # second call on the same plan: maxima start from zero again
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    res = out.cpu().numpy()
+    syn.close()
+    return res
+
+
+def compare_spreadout(oracle, S, G, bw_up, bw_out, tr, res, delay):
+    for b in range(tr.shape[0]):
+        st, sp = oracle.spreadout(S, G, bw_up, bw_out, tr[b], delay=delay)
+        if st != 0:
+            assert (res[b] == -1.0).all(), f"matrix {b}: negative entry not reported"
+        else:
+            np.testing.assert_allclose(res[b], sp, rtol=1e-9, atol=0.0, err_msg=f"matrix {b}")
+
+
+@pytest.mark.parametrize("ci,B", [(1, 16), (2, 64), (3, 16), (4, 8), (5, 3)])
+def test_spreadout_configs(oracle, torch_cuda, ci, B):
+    from paper_2505_09764_amd import workloads as W
+    w = W.config(ci)
+    say(f"[spreadout] {w.name} B={B}")
+    dev_t = W.generate_device(w, B)
+    host_t = dev_t.cpu().numpy()
+    for delay in (0.0, 2.5e-6):
+        res = run_spreadout(torch_cuda, w.S, w.G, w.bw_up, w.bw_out, dev_t, delay)
+        compare_spreadout(oracle, w.S, w.G, w.bw_up, w.bw_out, host_t, res, delay)
+
+
+@pytest.mark.parametrize("S,G", [(1, 1), (1, 8), (2, 1), (3, 3), (5, 7), (9, 6), (33, 2), (65, 1),
+                                 (100, 3), (128, 4)])
+def test_spreadout_random_shapes(oracle, torch_cuda, S, G):
+    rng = np.random.default_rng(7 * S + G)
+    kinds = ["uniform", "heavy", "sparse", "big"]
+    tr = np.stack([_rand(rng, S, G, kinds[b % 4]) for b in range(4)])
+    tr[np.arange(4)[:, None], np.arange(S * G), np.arange(S * G)] = -5      # diagonal ignored
+    if S * G > 2:
+        tr[3, 0, S * G - 1] = -1                                            # negative entry
+    say(f"[spreadout] random S={S} G={G}")
+    res = run_spreadout(torch_cuda, S, G, 450e9, 50e9, tr, 1e-6)
+    compare_spreadout(oracle, S, G, 450e9, 50e9, tr, res, 1e-6)
+
+
+def test_wakeup_delay_in_predicted_time(oracle, torch_cuda):
+    from paper_2505_09764_amd.binding import Synthesizer
+    from paper_2505_09764_amd import workloads as W
+    torch = torch_cuda
+    w = W.config(3)
+    tr = W.generate_host(w, 5)
+    tr[4] = 0                                   # nothing to send: no step, no delay
+    say("[parity] wake-up delay, cfg3 B=5")
+    syn = Synthesizer(w.S, w.G, w.bw_up, w.bw_out)
+    syn.set_wakeup_delay(4e-6)
+    out = syn.synthesize(torch.from_numpy(tr).cuda())
+    torch.cuda.synchronize()
+    times = out.predicted_time.cpu().numpy()
+    for b in range(5):
+        p = oracle.synthesize(w.S, w.G, w.bw_up, w.bw_out, tr[b], delay=4e-6)
+        np.testing.assert_allclose(times[b], p.time4, rtol=1e-9, atol=0.0)
+    assert times[4][0] == 0.0
+    syn.close()
