@@ -14,6 +14,7 @@ quoted on.  Prints ONE JSON line:
   stage_loop     the decomposition kernel, which is bound by its serial stage chain
   cpu_baseline   the CPU oracle timed on this machine's host cores on a bounded sample
   latency_b1     the same configuration at B = 1 (true single-matrix latency)
+  spreadout_baseline  time of the SpreadOut comparison pass and predicted-time ratios
 """
 import argparse
 import json
@@ -160,6 +161,25 @@ def main():
                "kernels_ms": [sum(k[i] for k in k1ms) / len(k1ms) for i in range(3)]}
         syn1.close()
 
+    # SpreadOut baseline (comparison schedule of the paper's simulation): one streaming pass
+    spo_out = syn.spreadout(traffic)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    nspo = max(3, min(args.steps, 10))
+    e0.record()
+    for _ in range(nspo):
+        syn.spreadout(traffic, spo_out)
+    e1.record()
+    torch.cuda.synchronize()
+    spo_ms = e0.elapsed_time(e1) / nspo
+    tp = out.predicted_time.cpu().numpy()
+    sp = spo_out.cpu().numpy()
+    spo = {"ms_per_call": spo_ms, "algorithmic_bytes": B * 8 * N * N,
+           "achieved_GBs": B * 8 * N * N / (spo_ms * 1e-3) / 1e9,
+           "mean_T_fast_over_t_opt": float((tp[:, 0] / tp[:, 3]).mean()),
+           "mean_T_spreadout_gpu_over_t_opt": float((sp[:, 0] / tp[:, 3]).mean()),
+           "mean_T_spreadout_server_over_t_opt": float((sp[:, 1] / tp[:, 3]).mean())}
+
     cpu = None
     if not args.no_cpu:
         host = traffic[:32].cpu().numpy()
@@ -195,6 +215,7 @@ def main():
                        "algorithmic_bytes": k2_bytes},
         "end_to_end_GBs": (k1_bytes + k2_bytes + k3_bytes) / (ms_per_step * 1e-3) / 1e9,
         "latency_b1": lat,
+        "spreadout_baseline": spo,
         "cpu_baseline": cpu,
     }
     syn.close()
