@@ -143,6 +143,23 @@ int fast_spreadout_batched(fast_plan_t *plan, int B, const int64_t *traffic,
                            double *out_spreadout_time, hipStream_t stream);
 
 /*
+ * Builds traffic matrices from per-expert token counts (Section 5 "Integration into MoE
+ * systems": the all-gathered counts that MoE frameworks hold before every dispatch).
+ *   tokens_per_expert  device, [B][N][E] int64; [b][src][e] = tokens GPU src routes to expert e
+ *   expert_to_gpu      device, [B][E] int32; GPU (0..N-1) that hosts expert e in matrix b
+ *   token_bytes        bytes per routed token (> 0)
+ *   out_traffic        device, [B][N][N]; out_traffic[b][src][h] = token_bytes * sum of the
+ *                      counts of the experts placed on GPU h; the diagonal holds what stays
+ *                      on the GPU (fast_synthesize_batched ignores it)
+ *   out_status         device, [B] int32; 0, or -1 if a count is negative or an expert is
+ *                      placed outside 0..N-1 (out_traffic of that matrix is unspecified)
+ * E >= 1.  Enqueued on `stream`, asynchronous; needs no workspace.
+ */
+int fast_build_traffic_batched(fast_plan_t *plan, int B, int E, const int64_t *tokens_per_expert,
+                               const int32_t *expert_to_gpu, int64_t token_bytes,
+                               int64_t *out_traffic, int32_t *out_status, hipStream_t stream);
+
+/*
  * Per-kernel timing for measurement.  fast_plan_set_timing(plan, 1) starts a new
  * recording (dropping any earlier one): each following fast_synthesize_batched call,
  * up to FAST_MAX_TIMED_CALLS of them, records HIP events on its stream around its

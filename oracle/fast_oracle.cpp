@@ -430,6 +430,30 @@ int spreadout(int S, int G, double bw_up, double bw_out, double delay, const i64
     return 0;
 }
 
+// ---------------------------------------------------------------------------
+// Traffic-matrix construction (Section 5 "Integration into MoE systems": the
+// All-Gather of per-expert token counts that MoE frameworks already perform gives
+// every rank counts[src][e] = tokens GPU src routes to expert e, "from which the
+// full traffic matrix can be constructed"): traffic[src][h] = token_bytes * sum of
+// counts[src][e] over the experts e placed on GPU h.  The diagonal holds what
+// stays on the GPU (the scheduler ignores it).  Returns -1 if a count is negative
+// or an expert is mapped outside 0..N-1 (traffic is then unspecified).
+// ---------------------------------------------------------------------------
+int build_traffic(int N, int E, const i64* counts, const int32_t* expert_to_gpu, i64 token_bytes,
+                  i64* traffic) {
+    for (int e = 0; e < E; ++e)
+        if (expert_to_gpu[e] < 0 || expert_to_gpu[e] >= N) return -1;
+    for (int src = 0; src < N; ++src) {
+        for (int h = 0; h < N; ++h) traffic[(size_t)src * N + h] = 0;
+        for (int e = 0; e < E; ++e) {
+            const i64 c = counts[(size_t)src * E + e];
+            if (c < 0) return -1;
+            traffic[(size_t)src * N + expert_to_gpu[e]] += c * token_bytes;
+        }
+    }
+    return 0;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -464,6 +488,11 @@ void oracle_cost(int S, int G, double bw_up, double bw_out, double delay, const 
                  const int64_t* X, const int64_t* intra_out, const int64_t* intra_in, int K,
                  const int64_t* bytes, double* out4, double* extra3) {
     cost(S, G, bw_up, bw_out, delay, T, X, intra_out, intra_in, K, bytes, out4, extra3);
+}
+
+int oracle_build_traffic(int N, int E, const int64_t* counts, const int32_t* expert_to_gpu,
+                         int64_t token_bytes, int64_t* traffic) {
+    return build_traffic(N, E, counts, expert_to_gpu, token_bytes, traffic);
 }
 
 int oracle_spreadout(int S, int G, double bw_up, double bw_out, double delay,

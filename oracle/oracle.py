@@ -60,6 +60,9 @@ def lib():
         L.oracle_spreadout.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double,
                                        ctypes.c_double, _i64p, _f64p]
         L.oracle_spreadout.restype = ctypes.c_int
+        L.oracle_build_traffic.argtypes = [ctypes.c_int, ctypes.c_int, _i64p, _i32p, ctypes.c_int64,
+                                           _i64p]
+        L.oracle_build_traffic.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -195,3 +198,13 @@ def spreadout(S, G, bw_up, bw_out, traffic, delay=0.0):
     out2 = np.zeros(2, np.float64)
     st = lib().oracle_spreadout(S, G, bw_up, bw_out, delay, _p64(traffic), _pf(out2))
     return st, out2
+
+
+def build_traffic(counts, expert_to_gpu, token_bytes):
+    """counts[N,E], expert_to_gpu[E] -> (status, traffic[N,N])"""
+    counts = _c64(counts)
+    N, E = counts.shape
+    m = np.ascontiguousarray(expert_to_gpu, dtype=np.int32)
+    out = np.zeros((N, N), np.int64)
+    st = lib().oracle_build_traffic(N, E, _p64(counts), _p32(m), int(token_bytes), _p64(out))
+    return st, out

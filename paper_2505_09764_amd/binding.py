@@ -22,7 +22,7 @@ FAST_STATUS_STAGE_OVERFLOW = -2
 FAST_STATUS_INTERNAL = -3
 
 EXPORTS = ("fast_plan_create", "fast_plan_max_stages", "fast_synthesize_batched",
-           "fast_plan_set_wakeup_delay", "fast_spreadout_batched",
+           "fast_plan_set_wakeup_delay", "fast_spreadout_batched", "fast_build_traffic_batched",
            "fast_plan_set_timing", "fast_plan_timed_calls", "fast_plan_kernel_ms",
            "fast_plan_destroy")
 
@@ -56,6 +56,9 @@ def lib():
         L.fast_plan_set_wakeup_delay.restype = ctypes.c_int
         L.fast_spreadout_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp]
         L.fast_spreadout_batched.restype = ctypes.c_int
+        L.fast_build_traffic_batched.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, vp,
+                                                 ctypes.c_int64, vp, vp, vp]
+        L.fast_build_traffic_batched.restype = ctypes.c_int
         L.fast_plan_set_timing.argtypes = [vp, ctypes.c_int]
         L.fast_plan_set_timing.restype = ctypes.c_int
         L.fast_plan_timed_calls.argtypes = [vp]
@@ -103,6 +106,15 @@ def fast_spreadout_batched(plan, B, traffic, out_spreadout_time, stream):
     rc = lib().fast_spreadout_batched(plan, int(B), traffic, out_spreadout_time, stream)
     if rc != FAST_OK:
         raise FastError("fast_spreadout_batched", rc)
+
+
+def fast_build_traffic_batched(plan, B, E, tokens_per_expert, expert_to_gpu, token_bytes,
+                               out_traffic, out_status, stream):
+    """Raw call: buffer arguments are device addresses (int), stream a hipStream_t (int)."""
+    rc = lib().fast_build_traffic_batched(plan, int(B), int(E), tokens_per_expert, expert_to_gpu,
+                                          int(token_bytes), out_traffic, out_status, stream)
+    if rc != FAST_OK:
+        raise FastError("fast_build_traffic_batched", rc)
 
 
 def fast_plan_set_timing(plan, enable):
@@ -191,6 +203,27 @@ class Synthesizer:
             stream = torch.cuda.current_stream(self.device).cuda_stream
             fast_spreadout_batched(self.plan, B, traffic.data_ptr(), out.data_ptr(), stream)
         return out
+
+    def build_traffic(self, tokens_per_expert, expert_to_gpu, token_bytes):
+        """counts int64 [B, N, E], placement int32 [B, E] -> (traffic int64 [B, N, N], status
+        int32 [B])."""
+        import torch
+        N = self.S * self.G
+        c, m = tokens_per_expert, expert_to_gpu
+        if c.dtype != torch.int64 or c.dim() != 3 or c.shape[1] != N or not c.is_contiguous():
+            raise ValueError(f"tokens_per_expert must be contiguous int64 [B, {N}, E]")
+        B, _, E = c.shape
+        if m.dtype != torch.int32 or tuple(m.shape) != (B, E) or not m.is_contiguous():
+            raise ValueError("expert_to_gpu must be contiguous int32 [B, E]")
+        if c.device != self.device or m.device != self.device:
+            raise ValueError("inputs must be on the plan's device")
+        traffic = torch.empty((B, N, N), dtype=torch.int64, device=self.device)
+        status = torch.empty((B,), dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+            fast_build_traffic_batched(self.plan, B, E, c.data_ptr(), m.data_ptr(), token_bytes,
+                                       traffic.data_ptr(), status.data_ptr(), stream)
+        return traffic, status
 
     def set_timing(self, enable):
         fast_plan_set_timing(self.plan, enable)

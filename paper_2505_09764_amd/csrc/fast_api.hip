@@ -12,6 +12,7 @@
 #include "k2_birkhoff.hpp"
 #include "k3_cost.hpp"
 #include "k4_spreadout.hpp"
+#include "k5_build_traffic.hpp"
 
 using fastk::i64;
 
@@ -296,6 +297,24 @@ int fast_spreadout_batched(fast_plan_t* p, int B, const int64_t* traffic,
     hipLaunchKernelGGL(fastk::spo_finish, dim3(B), dim3(fastk::SPO_THREADS),
                        (size_t)N * sizeof(double), stream, p->spoDiag, p->spoT, p->spoNeg,
                        out_spreadout_time, p->S, p->G, chunks, p->bw_up, p->bw_out, p->delay);
+    if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
+    return FAST_OK;
+}
+
+int fast_build_traffic_batched(fast_plan_t* p, int B, int E, const int64_t* tokens_per_expert,
+                               const int32_t* expert_to_gpu, int64_t token_bytes,
+                               int64_t* out_traffic, int32_t* out_status, hipStream_t stream) {
+    if (!p || B < 0 || E < 1 || token_bytes <= 0) return FAST_ERR_INVALID_ARG;
+    if (B == 0) return FAST_OK;
+    if (!tokens_per_expert || !expert_to_gpu || !out_traffic || !out_status)
+        return FAST_ERR_INVALID_ARG;
+    if (B > 65535) return FAST_ERR_UNSUPPORTED;
+    const int N = p->S * p->G;
+    hipLaunchKernelGGL(fastk::bt_zero, dim3((B + 255) / 256), dim3(256), 0, stream, out_status, B);
+    hipLaunchKernelGGL(fastk::bt_build, dim3(N, B), dim3(fastk::BT_THREADS),
+                       (size_t)N * sizeof(i64), stream,
+                       reinterpret_cast<const i64*>(tokens_per_expert), expert_to_gpu,
+                       reinterpret_cast<i64*>(out_traffic), out_status, N, E, (i64)token_bytes);
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     return FAST_OK;
 }

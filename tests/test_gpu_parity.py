@@ -334,3 +334,33 @@ def test_wakeup_delay_in_predicted_time(oracle, torch_cuda):
         np.testing.assert_allclose(times[b], p.time4, rtol=1e-9, atol=0.0)
     assert times[4][0] == 0.0
     syn.close()
+
+
+# ----------------------------------------------------------------------------
+# traffic-matrix construction from per-expert token counts
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("S,G,E", [(1, 1, 1), (2, 4, 8), (4, 8, 64), (3, 5, 47), (16, 8, 256),
+                                   (128, 8, 1024), (33, 2, 700)])
+def test_build_traffic(oracle, torch_cuda, S, G, E):
+    from paper_2505_09764_amd.binding import Synthesizer
+    torch = torch_cuda
+    N = S * G
+    B = 5 if N <= 256 else 3
+    rng = np.random.default_rng(N * 1000 + E)
+    counts = rng.integers(0, 5000, size=(B, N, E)).astype(np.int64)
+    counts[0] *= rng.random((N, E)) < 0.05                      # sparse routing
+    place = np.stack([rng.permutation(E) % N for _ in range(B)]).astype(np.int32)
+    if B > 2 and E > 1:
+        counts[1, N // 2, E - 1] = -3                           # bad count
+        place[2, 0] = N                                         # bad placement
+    say(f"[build] S={S} G={G} E={E} B={B}")
+    syn = Synthesizer(S, G, 400e9, 50e9)
+    t, st = syn.build_traffic(torch.from_numpy(counts).cuda(), torch.from_numpy(place).cuda(), 14336)
+    torch.cuda.synchronize()
+    t, st = t.cpu().numpy(), st.cpu().numpy()
+    for b in range(B):
+        ost, ot = oracle.build_traffic(counts[b], place[b], 14336)
+        assert st[b] == ost, f"matrix {b}: status {st[b]} != {ost}"
+        if ost == 0:
+            assert np.array_equal(t[b], ot), f"matrix {b}: traffic differs"
+    syn.close()
