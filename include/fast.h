@@ -143,6 +143,22 @@ int fast_spreadout_batched(fast_plan_t *plan, int B, const int64_t *traffic,
                            double *out_spreadout_time, hipStream_t stream);
 
 /*
+ * Execution order of the stages of synthesised plans (Appendix, proof of Theorem 2: stages
+ * are executed in ascending order of their transfer size, so that each stage's
+ * redistribution hides under the next one; the completion-time model assumes this order).
+ *   stage_bytes      device, [B][max_stages][S], as written by fast_synthesize_batched
+ *   num_stages       device, [B], as written by fast_synthesize_batched
+ *   out_stage_order  device, [B][max_stages] int32; entries 0..K-1 receive the stage indices
+ *                    by ascending stage weight (largest per-lane byte count of the stage),
+ *                    equal weights in extraction order; entries >= K, and all entries of a
+ *                    matrix whose num_stages is negative, are left untouched
+ * Enqueued on `stream`, asynchronous; uses its own part of the plan's workspace.
+ */
+int fast_stage_order_batched(fast_plan_t *plan, int B, const int64_t *stage_bytes,
+                             const int32_t *num_stages, int32_t *out_stage_order,
+                             hipStream_t stream);
+
+/*
  * Builds traffic matrices from per-expert token counts (Section 5 "Integration into MoE
  * systems": the all-gathered counts that MoE frameworks hold before every dispatch).
  *   tokens_per_expert  device, [B][N][E] int64; [b][src][e] = tokens GPU src routes to expert e

@@ -431,6 +431,30 @@ int spreadout(int S, int G, double bw_up, double bw_out, double delay, const i64
 }
 
 // ---------------------------------------------------------------------------
+// Execution order of the stages (Appendix, proof of Theorem 2: the stages are
+// sorted in ascending order of their transfer size and executed in that order, so
+// that each stage's redistribution hides under the next, larger, stage).  The
+// weight of stage s is its largest per-lane byte count; order[] lists the stage
+// indices by ascending weight, equal weights in extraction order.
+// ---------------------------------------------------------------------------
+void stage_order(int S, int K, const i64* bytes, int32_t* order) {
+    std::vector<i64> c(K > 0 ? K : 0);
+    for (int s = 0; s < K; ++s) {
+        i64 m = 0;
+        for (int a = 0; a < S; ++a) m = std::max(m, bytes[(size_t)s * S + a]);
+        c[s] = m;
+    }
+    for (int s = 0; s < K; ++s) order[s] = s;
+    // insertion sort: plainly stable
+    for (int i = 1; i < K; ++i) {
+        const int32_t x = order[i];
+        int j = i - 1;
+        while (j >= 0 && c[order[j]] > c[x]) { order[j + 1] = order[j]; --j; }
+        order[j + 1] = x;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Traffic-matrix construction (Section 5 "Integration into MoE systems": the
 // All-Gather of per-expert token counts that MoE frameworks already perform gives
 // every rank counts[src][e] = tokens GPU src routes to expert e, "from which the
@@ -488,6 +512,10 @@ void oracle_cost(int S, int G, double bw_up, double bw_out, double delay, const 
                  const int64_t* X, const int64_t* intra_out, const int64_t* intra_in, int K,
                  const int64_t* bytes, double* out4, double* extra3) {
     cost(S, G, bw_up, bw_out, delay, T, X, intra_out, intra_in, K, bytes, out4, extra3);
+}
+
+void oracle_stage_order(int S, int K, const int64_t* bytes, int32_t* order) {
+    stage_order(S, K, bytes, order);
 }
 
 int oracle_build_traffic(int N, int E, const int64_t* counts, const int32_t* expert_to_gpu,

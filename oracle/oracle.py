@@ -60,6 +60,8 @@ def lib():
         L.oracle_spreadout.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double,
                                        ctypes.c_double, _i64p, _f64p]
         L.oracle_spreadout.restype = ctypes.c_int
+        L.oracle_stage_order.argtypes = [ctypes.c_int, ctypes.c_int, _i64p, _i32p]
+        L.oracle_stage_order.restype = None
         L.oracle_build_traffic.argtypes = [ctypes.c_int, ctypes.c_int, _i64p, _i32p, ctypes.c_int64,
                                            _i64p]
         L.oracle_build_traffic.restype = ctypes.c_int
@@ -208,3 +210,14 @@ def build_traffic(counts, expert_to_gpu, token_bytes):
     out = np.zeros((N, N), np.int64)
     st = lib().oracle_build_traffic(N, E, _p64(counts), _p32(m), int(token_bytes), _p64(out))
     return st, out
+
+
+def stage_order(stage_bytes):
+    """stage_bytes[K,S] -> order[K] int32: stage indices by ascending weight, ties in
+    extraction order"""
+    by = _c64(stage_bytes)
+    K, S = by.shape
+    order = np.zeros(max(K, 1), np.int32)
+    if K:
+        lib().oracle_stage_order(S, K, _p64(by), _p32(order))
+    return order[:K]

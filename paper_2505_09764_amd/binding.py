@@ -23,6 +23,7 @@ FAST_STATUS_INTERNAL = -3
 
 EXPORTS = ("fast_plan_create", "fast_plan_max_stages", "fast_synthesize_batched",
            "fast_plan_set_wakeup_delay", "fast_spreadout_batched", "fast_build_traffic_batched",
+           "fast_stage_order_batched",
            "fast_plan_set_timing", "fast_plan_timed_calls", "fast_plan_kernel_ms",
            "fast_plan_destroy")
 
@@ -56,6 +57,8 @@ def lib():
         L.fast_plan_set_wakeup_delay.restype = ctypes.c_int
         L.fast_spreadout_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp]
         L.fast_spreadout_batched.restype = ctypes.c_int
+        L.fast_stage_order_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp]
+        L.fast_stage_order_batched.restype = ctypes.c_int
         L.fast_build_traffic_batched.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, vp,
                                                  ctypes.c_int64, vp, vp, vp]
         L.fast_build_traffic_batched.restype = ctypes.c_int
@@ -108,13 +111,22 @@ def fast_spreadout_batched(plan, B, traffic, out_spreadout_time, stream):
         raise FastError("fast_spreadout_batched", rc)
 
 
+def fast_stage_order_batched(plan, B, stage_bytes, num_stages, out_stage_order, stream):
+    """Raw call: buffer arguments are device addresses (int), stream a hipStream_t (int)."""
+    rc = lib().fast_stage_order_batched(plan, int(B), stage_bytes, num_stages, out_stage_order,
+                                        stream)
+    if rc != FAST_OK:
+        raise FastError("fast_stage_order_batched", rc)
+
+
 def fast_build_traffic_batched(plan, B, E, tokens_per_expert, expert_to_gpu, token_bytes,
                                out_traffic, out_status, stream):
     """Raw call: buffer arguments are device addresses (int), stream a hipStream_t (int)."""
     rc = lib().fast_build_traffic_batched(plan, int(B), int(E), tokens_per_expert, expert_to_gpu,
                                           int(token_bytes), out_traffic, out_status, stream)
     if rc != FAST_OK:
-        raise FastError("fast_build_traffic_batched", rc)
+        raise FastError("fast_build_traffic_batched",
+           "fast_stage_order_batched", rc)
 
 
 def fast_plan_set_timing(plan, enable):
@@ -203,6 +215,19 @@ class Synthesizer:
             stream = torch.cuda.current_stream(self.device).cuda_stream
             fast_spreadout_batched(self.plan, B, traffic.data_ptr(), out.data_ptr(), stream)
         return out
+
+    def stage_order(self, out, order=None):
+        """Execution order (ascending stage weight) of the plans in `out` (an Outputs
+        filled by synthesize) -> int32 tensor [B, max_stages]; entries >= K untouched."""
+        import torch
+        B = out.num_stages.shape[0]
+        if order is None:
+            order = torch.full((B, self.max_stages), -1, dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+            fast_stage_order_batched(self.plan, B, out.stage_bytes.data_ptr(),
+                                     out.num_stages.data_ptr(), order.data_ptr(), stream)
+        return order
 
     def build_traffic(self, tokens_per_expert, expert_to_gpu, token_bytes):
         """counts int64 [B, N, E], placement int32 [B, E] -> (traffic int64 [B, N, N], status

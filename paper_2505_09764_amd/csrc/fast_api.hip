@@ -13,6 +13,7 @@
 #include "k3_cost.hpp"
 #include "k4_spreadout.hpp"
 #include "k5_build_traffic.hpp"
+#include "k6_stage_order.hpp"
 
 using fastk::i64;
 
@@ -33,6 +34,10 @@ struct fast_plan {
     fastk::u64* spoDiag;   // [B][2][N] per-diagonal maxima
     i64* spoT;             // [B][S][S]
     int* spoNeg;           // [B][chunks]
+    // workspace of the stage-order sort for `so_cap_B` matrices
+    int so_cap_B;
+    fastk::u64* soKeys;    // [B][P]
+    int32_t* soIdx;        // [B][P]
     // timing: four events per recorded call
     int timing;
     int n_timed;
@@ -164,6 +169,9 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     p->spoDiag = nullptr;
     p->spoT = nullptr;
     p->spoNeg = nullptr;
+    p->so_cap_B = 0;
+    p->soKeys = nullptr;
+    p->soIdx = nullptr;
     p->timing = 0;
     p->n_timed = 0;
     p->ev = nullptr;
@@ -301,6 +309,37 @@ int fast_spreadout_batched(fast_plan_t* p, int B, const int64_t* traffic,
     return FAST_OK;
 }
 
+int fast_stage_order_batched(fast_plan_t* p, int B, const int64_t* stage_bytes,
+                             const int32_t* num_stages, int32_t* out_stage_order,
+                             hipStream_t stream) {
+    if (!p || B < 0) return FAST_ERR_INVALID_ARG;
+    if (B == 0) return FAST_OK;
+    if (!stage_bytes || !num_stages || !out_stage_order) return FAST_ERR_INVALID_ARG;
+    if (B > 65535) return FAST_ERR_UNSUPPORTED;
+    const int P = next_pow2(p->max_stages);
+    if (B > p->so_cap_B) {
+        if (p->soKeys) (void)hipFree(p->soKeys);
+        p->soKeys = nullptr;
+        p->so_cap_B = 0;
+        unsigned char* base = nullptr;
+        if (hipMalloc(&base, (size_t)B * P * (sizeof(i64) + sizeof(int32_t))) != hipSuccess) {
+            (void)hipGetLastError();
+            return FAST_ERR_OOM;
+        }
+        p->soKeys = reinterpret_cast<fastk::u64*>(base);
+        p->soIdx = reinterpret_cast<int32_t*>(p->soKeys + (size_t)B * P);
+        p->so_cap_B = B;
+    }
+    const int per = fastk::SO_W_THREADS / 64;
+    hipLaunchKernelGGL(fastk::so_weights, dim3((P + per - 1) / per, B), dim3(fastk::SO_W_THREADS),
+                       0, stream, reinterpret_cast<const i64*>(stage_bytes), num_stages,
+                       p->soKeys, p->soIdx, p->S, p->max_stages, P);
+    hipLaunchKernelGGL(fastk::so_sort, dim3(B), dim3(fastk::SO_THREADS), 0, stream, p->soKeys,
+                       p->soIdx, num_stages, out_stage_order, p->max_stages, P);
+    if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
+    return FAST_OK;
+}
+
 int fast_build_traffic_batched(fast_plan_t* p, int B, int E, const int64_t* tokens_per_expert,
                                const int32_t* expert_to_gpu, int64_t token_bytes,
                                int64_t* out_traffic, int32_t* out_status, hipStream_t stream) {
@@ -347,6 +386,7 @@ void fast_plan_destroy(fast_plan_t* p) {
     if (!p) return;
     free_workspace(p);
     free_spo_workspace(p);
+    if (p->soKeys) (void)hipFree(p->soKeys);
     if (p->ev) {
         for (int c = 0; c < FAST_MAX_TIMED_CALLS; ++c)
             for (int k = 0; k < 4; ++k)

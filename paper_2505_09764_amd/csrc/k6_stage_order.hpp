@@ -1,0 +1,82 @@
+// Execution order of the stages (paper Appendix, proof of Theorem 2): the stages
+// of a plan are executed in ascending order of their transfer size, which is
+// what lets each stage's redistribution hide under the next stage and what the
+// completion-time model assumes.  order[b][.] lists the stage indices of matrix b
+// by ascending weight (largest per-lane byte count of the stage), equal weights
+// in extraction order.
+//
+// so_weights reads the stage rows once (HBM-bound, 8*S bytes per stage): one
+// wavefront per stage row, wave maximum, and writes (weight, index) keys padded
+// to a power of two with +infinity keys.  so_sort is a bitonic sort of those
+// keys by (weight, index) - a total order, so the result does not depend on the
+// sorting network - kept in global memory (L2-resident, 12 bytes per stage) with
+// one workgroup per matrix.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "k1_rebalance.hpp"
+
+namespace fastk {
+
+constexpr int SO_THREADS = 1024;
+constexpr int SO_W_THREADS = 256;
+
+// grid (ceil(P / 4), B): each of the 4 wavefronts of a workgroup takes one key slot
+__global__ void __launch_bounds__(SO_W_THREADS)
+so_weights(const i64* __restrict__ stage_bytes, const int32_t* __restrict__ num_stages,
+           u64* __restrict__ keys, int32_t* __restrict__ idx, int S, int max_stages, int P) {
+    const int b = blockIdx.y;
+    const int s = blockIdx.x * (SO_W_THREADS / 64) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (s >= P) return;
+    const int K = num_stages[b];
+    u64 key = ~0ull;
+    if (s < K) {
+        const i64* row = stage_bytes + ((size_t)b * max_stages + s) * S;
+        i64 m = 0;
+        for (int a = lane; a < S; a += 64) m = max(m, row[a]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) m = max(m, __shfl_xor(m, off, 64));
+        key = (u64)m;
+    }
+    if (lane == 0) {
+        keys[(size_t)b * P + s] = key;
+        idx[(size_t)b * P + s] = s;
+    }
+}
+
+__global__ void __launch_bounds__(SO_THREADS)
+so_sort(u64* __restrict__ keys, int32_t* __restrict__ idx, const int32_t* __restrict__ num_stages,
+        int32_t* __restrict__ order, int max_stages, int P) {
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int K = num_stages[b];
+    if (K <= 0) return;
+    u64* k = keys + (size_t)b * P;
+    int32_t* x = idx + (size_t)b * P;
+    // sort only the smallest power of two that holds the K real keys
+    int n = 1;
+    while (n < K) n <<= 1;
+    for (int kk = 2; kk <= n; kk <<= 1)
+        for (int j = kk >> 1; j > 0; j >>= 1) {
+            for (int t = tid; t < n; t += SO_THREADS) {
+                const int p = t ^ j;
+                if (p > t) {
+                    const u64 ka = k[t], kb = k[p];
+                    const int32_t ia = x[t], ib = x[p];
+                    const bool a_after_b = ka > kb || (ka == kb && ia > ib);
+                    const bool up = (t & kk) == 0;
+                    if (a_after_b == up) {
+                        k[t] = kb; k[p] = ka;
+                        x[t] = ib; x[p] = ia;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    int32_t* out = order + (size_t)b * max_stages;
+    for (int s = tid; s < K; s += SO_THREADS) out[s] = x[s];
+}
+
+}  // namespace fastk

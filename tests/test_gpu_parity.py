@@ -364,3 +364,37 @@ def test_build_traffic(oracle, torch_cuda, S, G, E):
         if ost == 0:
             assert np.array_equal(t[b], ot), f"matrix {b}: traffic differs"
     syn.close()
+
+
+# ----------------------------------------------------------------------------
+# execution order of the stages (ascending weight)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("ci,B", [(1, 16), (2, 32), (3, 8), (4, 6), (5, 2)])
+def test_stage_order(oracle, torch_cuda, ci, B):
+    from paper_2505_09764_amd.binding import Synthesizer
+    from paper_2505_09764_amd import workloads as W
+    torch = torch_cuda
+    w = W.config(ci)
+    say(f"[order] {w.name} B={B}")
+    t = W.generate_device(w, B)
+    if B > 2:
+        t[1, 0, w.N - 1] = -1                    # a matrix without a plan: its order row stays untouched
+        t[2] = 0                                 # K = 0
+    syn = Synthesizer(w.S, w.G, w.bw_up, w.bw_out)
+    out = syn.synthesize(t)
+    order = syn.stage_order(out)
+    order2 = syn.stage_order(out)
+    torch.cuda.synchronize()
+    assert torch.equal(order, order2)
+    Ks = out.num_stages.cpu().numpy()
+    o = order.cpu().numpy()
+    by = out.stage_bytes.cpu().numpy()
+    for b in range(B):
+        K = int(Ks[b])
+        if K < 0:
+            assert (o[b] == -1).all()
+            continue
+        want = oracle.stage_order(by[b, :K])
+        assert np.array_equal(o[b, :K], want), f"matrix {b}: order differs"
+        assert (o[b, K:] == -1).all()
+    syn.close()
