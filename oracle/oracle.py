@@ -31,12 +31,9 @@ def build(force=True):
 _lib = None
 
 
-def lib():
-    global _lib
-    if _lib is None:
-        if not os.path.exists(_LIB):
-            build()
-        L = ctypes.CDLL(_LIB)
+def _bind(path):
+    if True:
+        L = ctypes.CDLL(path)
         L.oracle_aggregate.argtypes = [ctypes.c_int, ctypes.c_int, _i64p, _i64p, _i64p, _i64p]
         L.oracle_aggregate.restype = ctypes.c_int
         L.oracle_rebalance_tile.argtypes = [ctypes.c_int, _i64p, _i64p, _i64p]
@@ -65,8 +62,35 @@ def lib():
         L.oracle_build_traffic.argtypes = [ctypes.c_int, ctypes.c_int, _i64p, _i32p, ctypes.c_int64,
                                            _i64p]
         L.oracle_build_traffic.restype = ctypes.c_int
-        _lib = L
+    return L
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build()
+        _lib = _bind(_LIB)
     return _lib
+
+
+class use_library:
+    """Context manager: route every call of this module to another build of the oracle
+    (used by the tests that plant mistakes in a copy of the source)."""
+
+    def __init__(self, path):
+        self.path = path
+
+    def __enter__(self):
+        global _lib
+        self.saved = _lib
+        _lib = _bind(self.path)
+        return self
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self.saved
+        return False
 
 
 def _p64(a):

@@ -123,6 +123,12 @@ def test_embedding_small_case(oracle):
     Q = np.array([[0, 4, 0], [0, 0, 0], [0, 0, 0]], dtype=np.int64)
     L, A = oracle.embed(Q)
     assert L == 4 and A.tolist() == [[0, 0, 0], [4, 0, 0], [0, 0, 4]]
+    # server 1 neither sends nor receives: its whole deficit goes on its own diagonal cell
+    # (virtual bytes never share a cell with real ones when that can be avoided), and only
+    # what is left is poured in index order
+    Q = np.array([[0, 0, 4], [0, 0, 0], [0, 0, 0]], dtype=np.int64)
+    L, A = oracle.embed(Q)
+    assert L == 4 and A.tolist() == [[0, 0, 0], [0, 4, 0], [4, 0, 0]]
 
 
 def test_uniform_all_to_all(oracle):
@@ -145,6 +151,7 @@ def test_uniform_all_to_all(oracle):
         assert p.time4[1] == 0.0                                   # nothing to balance
         assert p.time4[2] == pytest.approx((S - 1) * G * x / 50e9, rel=1e-15)
         assert p.extra3[0] == pytest.approx((G - 1) * x / 400e9, rel=1e-15)
+        assert p.extra3[1] == pytest.approx((G - 1) * G * x / 400e9, rel=1e-15)   # t3, factor (G-1) kept
 
 
 def test_negative_entry_and_diagonal(oracle):
