@@ -114,6 +114,8 @@ int grow_workspace(fast_plan* p, int B) {
     return FAST_OK;
 }
 
+static_assert(fastk::K1_MAX_S == FAST_MAX_SERVERS, "kernel 1 unrolls for FAST_MAX_SERVERS");
+
 template <int G>
 void launch_k1(const fast_plan* p, int B, const i64* traffic, i64* X, hipStream_t stream) {
     const dim3 grid(p->S, B), block(fastk::K1_THREADS);

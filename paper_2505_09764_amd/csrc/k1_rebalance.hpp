@@ -1,25 +1,32 @@
 // Kernel 1: server aggregation, sender balancing and collapse.
 //
 // One workgroup per (matrix b, source server a) handles the G x N row block of
-// the traffic matrix that belongs to server a:
-//   phase A  reads the block once and reduces every cross-server tile row to its
+// the traffic matrix that belongs to server a (64 KiB in, 64 KiB out at S = 128,
+// G = 8, both contiguous):
+//   phase A  reads the block once, 16 bytes per lane with consecutive lanes on
+//            consecutive addresses, and reduces every cross-server tile row to its
 //            row sum r_i(a,d) (paper Section 4.1 "Example setup": a tile's row
-//            sums are what each GPU sends to that server);
-//   phase B  per tile: tile total T[a][d], lane targets floor/ceil(T/G), each
-//            row's surplus or deficit and its position (prefix sum) among the
-//            tile's surpluses / deficits (Section 4.1 "Mitigating sender skew");
-//            the per-lane server entry Q[a][d] = ceil(T/G) of the merged peer
-//            transfer (Section 4.1 "Mitigating receiver skew", Section 4.2 Fig. 6);
-//   phase C  writes the lane-routing matrix X.  Pouring surpluses into deficits in
-//            ascending index order means surplus row i covers the byte interval
-//            [PS_i, PS_i + s_i) and deficit row k the interval [PD_k, PD_k + d_k)
-//            of the same line, so X[i][k] is the length of their intersection -
-//            every output element is independent of the others.
+//            sums are what each GPU sends to that server).  The G/2 lanes that
+//            share a tile row add their partial sums with DPP lane exchanges;
+//   phase B  one thread per tile: tile total T[a][d], lane targets floor/ceil(T/G),
+//            and in one ascending pass over the tile's rows each row's surplus or
+//            deficit and where it starts among the tile's surpluses / deficits
+//            (Section 4.1 "Mitigating sender skew"); the per-lane server entry
+//            Q[a][d] = ceil(T/G) of the merged peer transfer (Section 4.1
+//            "Mitigating receiver skew", Section 4.2 Fig. 6);
+//   phase C  writes the lane-routing matrix X, again 16 bytes per lane.  Pouring
+//            surpluses into deficits in ascending index order means surplus row i
+//            covers the byte interval [PS_i, PS_i + s_i) and deficit row k the
+//            interval [PD_k, PD_k + d_k) of the same line, so X[i][k] is the length
+//            of their intersection - every output element is independent of the
+//            others.  Two surplus rows (or two deficit rows) never intersect, so
+//            only the sender's side needs the surplus test.
 // The block also leaves, for the cost model, the largest per-GPU hand-off
 // volume (balancing) and intra-server volume of its server.
 //
 // HBM traffic: the row block is read once (8*G*N bytes) and X written once
-// (8*G*N bytes); everything else lives in LDS.
+// (8*G*N bytes), both with the non-temporal hint since neither is touched again
+// by this kernel; everything else lives in LDS (3 tables of S*G words).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -28,11 +35,14 @@ namespace fastk {
 
 typedef long long i64;
 typedef unsigned long long u64;
+typedef long long ll2 __attribute__((ext_vector_type(2)));
 
 struct alignas(16) i64x2 { i64 x, y; };
 
 constexpr int K1_THREADS = 256;
+constexpr int K1_MAX_S = 128;            // FAST_MAX_SERVERS: bounds the unrolled per-thread work
 constexpr u64 K1_SURPLUS_BIT = 1ull << 63;
+constexpr int K1_SLOTS = 8;              // partial sums per block-wide total (spreads LDS atomics)
 
 // Per-block record left for kernels 2 and 3: [b][a][4]
 //   0: max over the server's GPUs of max(bytes handed off, bytes handed in)
@@ -42,7 +52,16 @@ constexpr u64 K1_SURPLUS_BIT = 1ull << 63;
 constexpr int K1_PART = 4;
 
 inline size_t k1_lds_bytes(int S, int G) {
-    return (size_t)S * G * 4 * sizeof(i64) + (size_t)(4 * G + 2) * sizeof(i64);
+    return (size_t)S * G * 3 * sizeof(i64) +
+           (size_t)((2 * G + 1) * K1_SLOTS + 2 * G + 2) * sizeof(i64);
+}
+
+// 64-bit value of the lane selected by DPP control CTRL (every lane has a source).
+template <int CTRL>
+__device__ __forceinline__ i64 dpp_i64(i64 x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(u64)x, CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)((u64)x >> 32), CTRL, 0xf, 0xf, false);
+    return (i64)(((u64)(unsigned)hi << 32) | (unsigned)lo);
 }
 
 template <int G, bool VEC>
@@ -50,168 +69,186 @@ __global__ void __launch_bounds__(K1_THREADS)
 k1_rebalance(const i64* __restrict__ traffic, i64* __restrict__ X, i64* __restrict__ wsT,
              i64* __restrict__ wsQ, i64* __restrict__ wsPart, int S) {
     extern __shared__ __align__(16) unsigned char k1_smem[];
+    constexpr int EPL = VEC ? 2 : 1;         // elements per lane
+    constexpr int LPR = G / EPL;             // lanes per tile row
+    constexpr bool POW2 = (LPR & (LPR - 1)) == 0;
+    constexpr int MAXIT = (K1_MAX_S * LPR + K1_THREADS - 1) / K1_THREADS;
     const int a = blockIdx.x;
     const int b = blockIdx.y;
     const int N = S * G;
-    const int P = S * G;                 // tile rows in the block, index p = d*G + i
-    i64* r = reinterpret_cast<i64*>(k1_smem);
-    u64* lo = reinterpret_cast<u64*>(r + P);
+    const int P = S * G;                     // tile rows of the block, index p = d*G + i
+    const int rowl = S * LPR;                // lanes per GPU row
+    u64* lo = reinterpret_cast<u64*>(k1_smem);
     i64* hi = reinterpret_cast<i64*>(lo + P);
-    i64* kept = hi + P;
-    i64* acc_out = kept + P;             // [G] bytes handed off per GPU
-    i64* acc_in = acc_out + G;           // [G] bytes handed in per GPU
-    i64* intra_in = acc_in + G;          // [G] intra-server bytes received per GPU
-    i64* intra_out = intra_in + G;       // [G]
-    i64* misc = intra_out + G;           // [0] negative flag, [1] sum_d T[a][d]
+    i64* kept = hi + P;                      // holds the tile row sums until phase B
+    u64* acc = reinterpret_cast<u64*>(kept + P);   // [(2G+1)][SLOTS]
+    i64* intra_in = reinterpret_cast<i64*>(acc + (2 * G + 1) * K1_SLOTS);
+    i64* intra_out = intra_in + G;
+    i64* misc = intra_out + G;               // [0] negative flag
     const int tid = threadIdx.x;
 
-    if (tid < 4 * G + 2) acc_out[tid] = 0;
+    for (int t = tid; t < (2 * G + 1) * K1_SLOTS + 2 * G + 2; t += K1_THREADS) acc[t] = 0;
+    if constexpr (!POW2) {
+        for (int t = tid; t < P; t += K1_THREADS) kept[t] = 0;
+    }
     __syncthreads();
 
     const i64* blk = traffic + ((size_t)b * N + (size_t)a * G) * N;
 
-    // ---- phase A: tile row sums.  Tile rows are taken in (i, d) order so that
-    // consecutive threads read consecutive tiles of one GPU row.
-    bool neg = false;
-    for (int t = tid; t < P; t += K1_THREADS) {
-        const int i = t / S;
-        const int d = t - i * S;
-        const i64* src = blk + (size_t)i * N + (size_t)d * G;
-        i64 v[G];
-        if constexpr (VEC) {
-            const i64x2* s2 = reinterpret_cast<const i64x2*>(src);
+    // ---- phase A: lane hp of GPU row i holds elements [hp*EPL, hp*EPL + EPL) of that row.
+    // All loads of IB rows are issued before the first one is consumed.
+    {
+        i64 orv = 0;
+        constexpr int IB = G >= 4 ? 4 : G;   // GPU rows whose loads are in flight together
 #pragma unroll
-            for (int j = 0; j < G / 2; ++j) {
-                const i64x2 w = s2[j];
-                v[2 * j] = w.x;
-                v[2 * j + 1] = w.y;
-            }
-        } else {
+        for (int i0 = 0; i0 < G; i0 += IB) {
+            i64 w[IB][MAXIT][EPL];
 #pragma unroll
-            for (int j = 0; j < G; ++j) v[j] = src[j];
-        }
-        i64 sum = 0;
-        if (d == a) {
+            for (int ii = 0; ii < IB; ++ii) {
 #pragma unroll
-            for (int j = 0; j < G; ++j) {
-                if (j != i) {                       // the GPU diagonal uses no link
-                    neg |= v[j] < 0;
-                    sum += v[j];
-                    atomicAdd(reinterpret_cast<u64*>(&intra_in[j]), (u64)v[j]);
+                for (int it = 0; it < MAXIT; ++it) {
+                    const int hp = tid + it * K1_THREADS;
+                    const i64* src = blk + (size_t)(i0 + ii) * N + (size_t)hp * EPL;
+                    if constexpr (VEC) {
+                        ll2 t = {0, 0};
+                        if (i0 + ii < G && hp < rowl) t = __builtin_nontemporal_load(reinterpret_cast<const ll2*>(src));
+                        w[ii][it][0] = t.x;
+                        w[ii][it][1] = t.y;
+                    } else {
+                        w[ii][it][0] = (i0 + ii < G && hp < rowl) ? __builtin_nontemporal_load(src) : 0;
+                    }
                 }
             }
-            intra_out[i] = sum;
-        } else {
 #pragma unroll
-            for (int j = 0; j < G; ++j) {
-                neg |= v[j] < 0;
-                sum += v[j];
+            for (int ii = 0; ii < IB; ++ii) {
+                const int i = i0 + ii;
+                if (i >= G) continue;
+#pragma unroll
+                for (int it = 0; it < MAXIT; ++it) {
+                    const int hp = tid + it * K1_THREADS;
+                    const int d = hp / LPR;
+                    const int k = (hp - d * LPR) * EPL;
+                    const bool live = hp < rowl;
+                    i64 sum = 0;
+                    if (live && d == a) {
+#pragma unroll
+                        for (int c = 0; c < EPL; ++c) {
+                            i64 x = w[ii][it][c];
+                            if (k + c == i) x = 0;      // the GPU diagonal uses no link
+                            orv |= x;
+                            sum += x;
+                            if (x) atomicAdd(reinterpret_cast<u64*>(&intra_in[k + c]), (u64)x);
+                        }
+                        if (sum) atomicAdd(reinterpret_cast<u64*>(&intra_out[i]), (u64)sum);
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < EPL; ++c) { orv |= w[ii][it][c]; sum += w[ii][it][c]; }
+                    }
+                    if constexpr (POW2) {
+                        if constexpr (LPR >= 2) sum += dpp_i64<0xB1>(sum);    // quad_perm [1,0,3,2]
+                        if constexpr (LPR >= 4) sum += dpp_i64<0x4E>(sum);    // quad_perm [2,3,0,1]
+                        if constexpr (LPR >= 8) sum += dpp_i64<0x141>(sum);   // row_half_mirror
+                        if (live && k == 0) kept[d * G + i] = sum;
+                    } else {
+                        if (live) atomicAdd(reinterpret_cast<u64*>(&kept[d * G + i]), (u64)sum);
+                    }
+                }
             }
         }
-        r[d * G + i] = sum;
+        if (orv < 0) misc[0] = 1;
     }
-    if (neg) misc[0] = 1;
     __syncthreads();
 
-    // ---- phase B: one thread per tile row (d, i)
-    for (int p = tid; p < P; p += K1_THREADS) {
-        const int d = p / G;
-        const int i = p - d * G;
+    // ---- phase B: one thread per tile (a, d); p = d*G + k indexes the tables
+    for (int d = tid; d < S; d += K1_THREADS) {
+        i64 tot = 0, Q = 0;
         if (d == a) {
-            lo[p] = 0;
-            hi[p] = 0;
-            kept[p] = 0;
-            if (i == 0) {
-                wsT[((size_t)b * S + a) * S + d] = 0;
-                wsQ[((size_t)b * S + a) * S + d] = 0;
-            }
-            continue;
-        }
-        i64 rr[G];
-        i64 tot = 0;
 #pragma unroll
-        for (int k = 0; k < G; ++k) {
-            rr[k] = r[d * G + k];
-            tot += rr[k];
-        }
-        const i64 q = tot / G;
-        const int rho = (int)(tot - q * G);
-        i64 ps = 0, pd = 0, my_s = 0, my_d = 0, my_t = 0;
-#pragma unroll
-        for (int k = 0; k < G; ++k) {
-            const i64 tk = q + (k < rho ? 1 : 0);
-            const i64 sk = rr[k] > tk ? rr[k] - tk : 0;
-            const i64 dk = tk > rr[k] ? tk - rr[k] : 0;
-            if (k < i) { ps += sk; pd += dk; }
-            if (k == i) { my_s = sk; my_d = dk; my_t = tk; }
-        }
-        if (my_s > 0) {
-            lo[p] = (u64)ps | K1_SURPLUS_BIT;
-            hi[p] = ps + my_s;
-            atomicAdd(reinterpret_cast<u64*>(&acc_out[i]), (u64)my_s);
+            for (int k = 0; k < G; ++k) { lo[d * G + k] = 0; hi[d * G + k] = 0; kept[d * G + k] = 0; }
         } else {
-            lo[p] = (u64)pd;
-            hi[p] = pd + my_d;
-            if (my_d > 0) atomicAdd(reinterpret_cast<u64*>(&acc_in[i]), (u64)my_d);
+            i64 rr[G];
+#pragma unroll
+            for (int k = 0; k < G; ++k) { rr[k] = kept[d * G + k]; tot += rr[k]; }
+            const i64 q = tot / G;
+            const int rho = (int)(tot - q * G);
+            Q = q + (rho > 0 ? 1 : 0);
+            i64 ps = 0, pd = 0;
+            const int slot = d & (K1_SLOTS - 1);
+#pragma unroll
+            for (int k = 0; k < G; ++k) {
+                const i64 tk = q + (k < rho ? 1 : 0);
+                const i64 diff = rr[k] - tk;
+                const bool surplus = diff > 0;
+                const i64 sk = surplus ? diff : 0;
+                const i64 dk = sk - diff;
+                const i64 base = surplus ? ps : pd;
+                lo[d * G + k] = (u64)base | (surplus ? K1_SURPLUS_BIT : 0ull);
+                hi[d * G + k] = base + (surplus ? sk : dk);
+                kept[d * G + k] = rr[k] - sk;
+                ps += sk;
+                pd += dk;
+                atomicAdd(&acc[k * K1_SLOTS + slot], (u64)sk);
+                atomicAdd(&acc[(G + k) * K1_SLOTS + slot], (u64)dk);
+            }
+            atomicAdd(&acc[2 * G * K1_SLOTS + slot], (u64)tot);
         }
-        kept[p] = rr[i] < my_t ? rr[i] : my_t;
-        if (i == 0) {
-            wsT[((size_t)b * S + a) * S + d] = tot;
-            wsQ[((size_t)b * S + a) * S + d] = q + (rho > 0 ? 1 : 0);
-            atomicAdd(reinterpret_cast<u64*>(&misc[1]), (u64)tot);
-        }
+        wsT[((size_t)b * S + a) * S + d] = tot;
+        wsQ[((size_t)b * S + a) * S + d] = Q;
     }
     __syncthreads();
 
-    if (tid == 0) {
-        i64 bal = 0, intra = 0;
-        for (int i = 0; i < G; ++i) {
-            bal = max(bal, max(acc_out[i], acc_in[i]));
-            intra = max(intra, max(intra_out[i], intra_in[i]));
+    if (tid >= K1_THREADS - 64) {
+        // last wave: lane j < 2G sums GPU j's hand-off (or hand-in) slots, lane 2G the tile totals
+        const int j = tid - (K1_THREADS - 64);
+        u64 s = 0;
+        if (j < 2 * G + 1) {
+#pragma unroll
+            for (int k = 0; k < K1_SLOTS; ++k) s += acc[j * K1_SLOTS + k];
+        }
+        i64 bal = j < 2 * G ? (i64)s : 0;
+        i64 intra = j < 2 * G ? intra_in[j] : 0;      // intra_in and intra_out are adjacent
+#pragma unroll
+        for (int m = 1; m < 16; m <<= 1) {
+            bal = max(bal, __shfl_xor(bal, m));
+            intra = max(intra, __shfl_xor(intra, m));
         }
         i64* part = wsPart + ((size_t)b * S + a) * K1_PART;
-        part[0] = bal;
-        part[1] = intra;
-        part[2] = misc[0];
-        part[3] = misc[1];
+        if (j == 0) { part[0] = bal; part[1] = intra; part[2] = misc[0]; }
+        if (j == 2 * G) part[3] = (i64)s;
     }
 
-    // ---- phase C: lane-routing matrix, coalesced along each GPU row
+    // ---- phase C: lane-routing matrix, same lane-to-element mapping as phase A
     i64* xblk = X + ((size_t)b * N + (size_t)a * G) * N;
-    auto cell = [&](int d, int i, int k, u64 lo_i, i64 hi_i, i64 kept_i) -> i64 {
-        if (d == a) return 0;
-        if (k == i) return kept_i;
-        if (!(lo_i & K1_SURPLUS_BIT)) return 0;      // a deficit row hands nothing off
-        const u64 lo_k = lo[d * G + k];
-        if (lo_k & K1_SURPLUS_BIT) return 0;         // a surplus row takes nothing in
-        const i64 l = max((i64)(lo_i & ~K1_SURPLUS_BIT), (i64)lo_k);
-        const i64 h = min(hi_i, hi[d * G + k]);
-        return h > l ? h - l : 0;
-    };
-    if constexpr (VEC) {
-        const int half = N / 2;
-        for (int e = tid; e < G * half; e += K1_THREADS) {
-            const int i = e / half;
-            const int h = (e - i * half) * 2;
-            const int d = h / G;
-            const int k = h - d * G;
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+#pragma unroll
+        for (int it = 0; it < MAXIT; ++it) {
+            const int hp = tid + it * K1_THREADS;
+            if (hp >= rowl) continue;
+            const int d = hp / LPR;
+            const int k = (hp - d * LPR) * EPL;
             const int p = d * G + i;
             const u64 lo_i = lo[p];
-            const i64 hi_i = hi[p];
+            const i64 slo = (i64)(lo_i & ~K1_SURPLUS_BIT);
+            const i64 shi = (lo_i & K1_SURPLUS_BIT) ? hi[p] : slo;   // a deficit row hands nothing off
             const i64 kept_i = kept[p];
-            i64x2 w;
-            w.x = cell(d, i, k, lo_i, hi_i, kept_i);
-            w.y = cell(d, i, k + 1, lo_i, hi_i, kept_i);
-            *reinterpret_cast<i64x2*>(xblk + (size_t)i * N + h) = w;
-        }
-    } else {
-        for (int e = tid; e < G * N; e += K1_THREADS) {
-            const int i = e / N;
-            const int h = e - i * N;
-            const int d = h / G;
-            const int k = h - d * G;
-            const int p = d * G + i;
-            xblk[(size_t)i * N + h] = cell(d, i, k, lo[p], hi[p], kept[p]);
+            i64 out[EPL];
+#pragma unroll
+            for (int c = 0; c < EPL; ++c) {
+                const i64 lk = (i64)(lo[d * G + k + c] & ~K1_SURPLUS_BIT);
+                const i64 hk = hi[d * G + k + c];
+                const i64 l = max(slo, lk);
+                const i64 h = min(shi, hk);
+                const i64 w = h - l;
+                out[c] = (k + c == i) ? kept_i : (w > 0 ? w : 0);
+            }
+            i64* dst = xblk + (size_t)i * N + (size_t)hp * EPL;
+            if constexpr (VEC) {
+                ll2 t = {out[0], out[1]};
+                __builtin_nontemporal_store(t, reinterpret_cast<ll2*>(dst));
+            } else {
+                __builtin_nontemporal_store(out[0], dst);
+            }
         }
     }
 }
