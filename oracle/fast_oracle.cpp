@@ -478,6 +478,165 @@ int build_traffic(int N, int E, const i64* counts, const int32_t* expert_to_gpu,
     return 0;
 }
 
+// ---------------------------------------------------------------------------
+// Which bytes travel where (Section 4.1 "Redistribution", Section 4.2 Step 3
+// "Per-stage redistribution"): after a stage's scale-out transfer the data sits on
+// the right server but possibly on the wrong GPU, and is forwarded over scale-up
+// from the proxy GPU (d,k) that received it to its destination GPU (d,j).
+//
+// The paper does not say which of a GPU's bytes are the ones handed to another
+// lane, nor in which order a lane sends what it holds, so a byte-identity policy is
+// fixed here:
+//  * the bytes GPU (a,i) holds for server d form one region, ordered by
+//    destination GPU: traffic[(a,i)][(d,0)] bytes for (d,0), then those for (d,1),
+//    ... ;
+//  * balancing: the GPU keeps the head of its region (as many bytes as it sends on
+//    its own lane) and hands off the tail; the tail is cut into the pieces of
+//    rebalance_tile() in ascending receiver index;
+//  * lane k's send queue for server d is what GPU (a,k) kept, followed by the
+//    pieces it was handed in ascending donor index;
+//  * every stage in which a sends to d takes the next bytes[s][a] bytes from the
+//    front of each lane's queue (a lane whose queue is one byte shorter, because
+//    the tile total is not a multiple of G, runs out one byte early).
+// lane_queues() builds the G queues of one tile as runs of equal destination.
+// ---------------------------------------------------------------------------
+struct Run { int dest; i64 len; };
+struct Queue {
+    std::vector<Run> runs;
+    size_t head = 0;       // first run not yet fully taken
+    i64 used = 0;          // bytes already taken from runs[head]
+    void push(const Run& r) { if (r.len > 0) runs.push_back(r); }
+    // Removes up to n bytes from the front and appends them to `out`.
+    void take(i64 n, Queue* out) {
+        while (n > 0 && head < runs.size()) {
+            const i64 avail = runs[head].len - used;
+            const i64 mv = std::min(avail, n);
+            out->push({runs[head].dest, mv});
+            used += mv;
+            n -= mv;
+            if (used == runs[head].len) { ++head; used = 0; }
+        }
+    }
+};
+
+// tile: G x G traffic tile of one ordered server pair, tile[i*G+j] = bytes (a,i) -> (d,j).
+void lane_queues(int G, const i64* tile, std::vector<Queue>* queue) {
+    std::vector<Queue> region(G);
+    std::vector<i64> r(G, 0);
+    i64 tot = 0;
+    for (int i = 0; i < G; ++i)
+        for (int j = 0; j < G; ++j) {
+            region[i].push({j, tile[i * G + j]});
+            r[i] += tile[i * G + j];
+            tot += tile[i * G + j];
+        }
+    const i64 q = tot / G, rho = tot % G;
+    std::vector<i64> s(G), d(G);
+    queue->assign(G, Queue());
+    for (int k = 0; k < G; ++k) {
+        const i64 target = q + (k < rho ? 1 : 0);
+        s[k] = std::max<i64>(0, r[k] - target);
+        d[k] = std::max<i64>(0, target - r[k]);
+        region[k].take(std::min(r[k], target), &(*queue)[k]);   // the head stays on lane k
+    }
+    int i = 0, k = 0;                                           // the tails are poured as in rebalance_tile()
+    while (i < G && k < G) {
+        if (s[i] == 0) { ++i; continue; }
+        if (d[k] == 0) { ++k; continue; }
+        const i64 mv = std::min(s[i], d[k]);
+        region[i].take(mv, &(*queue)[k]);
+        s[i] -= mv;
+        d[k] -= mv;
+    }
+}
+
+// Plays the K stages in execution order (order[e] = e-th stage to run; NULL = the
+// order they were extracted in) and records, per stage s and source server a:
+//   offsets[s][a]    per-lane bytes a had already sent to stages[s][a] before s
+//                    (0 where a is idle in s);
+//   redis_bytes[s]   scale-up volume of the stage's redistribution = the largest,
+//                    over the GPUs of all receiving servers, of max(bytes the GPU
+//                    forwards to other GPUs, bytes it is forwarded by others);
+//   for each selected stage sel[q], sel_out[q][d][k][j] = bytes that arrived at
+//   server d on lane k in that stage and belong to GPU (d,j) (zero tile if no
+//   server sends to d in that stage).
+void redistribution(int S, int G, const i64* traffic, int K, const int32_t* stages, const i64* bytes,
+                    const int32_t* order, i64* offsets, i64* redis_bytes, int n_sel,
+                    const int32_t* sel, i64* sel_out) {
+    const int N = S * G;
+    std::vector<std::vector<Queue>> queues((size_t)S * S);
+    std::vector<i64> sent((size_t)S * S, 0), tile((size_t)G * G), M((size_t)G * G);
+    for (int a = 0; a < S; ++a)
+        for (int d = 0; d < S; ++d) {
+            if (a == d) continue;
+            for (int i = 0; i < G; ++i)
+                for (int j = 0; j < G; ++j) tile[i * G + j] = at(traffic, N, a * G + i, d * G + j);
+            lane_queues(G, tile.data(), &queues[(size_t)a * S + d]);
+        }
+    if (n_sel > 0) std::fill(sel_out, sel_out + (size_t)n_sel * S * G * G, (i64)0);
+    for (int e = 0; e < K; ++e) {
+        const int s = order ? order[e] : e;
+        i64 worst = 0;
+        for (int a = 0; a < S; ++a) {
+            const int d = stages[(size_t)s * S + a];
+            offsets[(size_t)s * S + a] = 0;
+            if (d < 0) continue;
+            const i64 len = bytes[(size_t)s * S + a];
+            offsets[(size_t)s * S + a] = sent[(size_t)a * S + d];
+            sent[(size_t)a * S + d] += len;
+            std::fill(M.begin(), M.end(), (i64)0);
+            for (int k = 0; k < G; ++k) {
+                Queue got;
+                queues[(size_t)a * S + d][k].take(len, &got);
+                for (const Run& run : got.runs) M[k * G + run.dest] += run.len;
+            }
+            for (int g = 0; g < G; ++g) {
+                i64 fwd = 0, recv = 0;
+                for (int o = 0; o < G; ++o) {
+                    if (o == g) continue;
+                    fwd += M[g * G + o];     // arrived at g, belongs to o
+                    recv += M[o * G + g];    // arrived at o, belongs to g
+                }
+                worst = std::max(worst, std::max(fwd, recv));
+            }
+            for (int q = 0; q < n_sel; ++q)
+                if (sel[q] == s)
+                    std::copy(M.begin(), M.end(), sel_out + ((size_t)q * S + d) * G * G);
+        }
+        redis_bytes[s] = worst;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Completion time of the overlapped pipeline (Section 4.3 "Pipeline structure"):
+// balancing runs first; then the scale-out stages run back to back; the
+// intra-server portion of the All-to-All runs on the scale-up fabric alongside the
+// first stage; stage i's redistribution starts when stage i's scale-out has ended
+// and the scale-up fabric is free (it is used by one thing at a time: the
+// intra-server portion, then the redistributions in stage order), overlapping
+// the following stages; the last redistribution has nothing to hide under.
+// Every step that moves bytes costs the wake-up delay plus bytes / bandwidth
+// (Section 5.4).  weight[e] / redis[e] are the e-th executed stage's per-lane
+// scale-out bytes and its redistribution's scale-up bytes.
+//   out2[0] = completion time, out2[1] = time at which the last scale-out ends.
+// ---------------------------------------------------------------------------
+void pipeline_time(double bw_up, double bw_out, double delay, i64 bal, i64 intra, int K,
+                   const i64* weight, const i64* redis, double* out2) {
+    double t = 0.0;
+    if (bal > 0) t = delay + (double)bal / bw_up;
+    double out_end = t, up_free = t;
+    if (intra > 0) up_free = t + (delay + (double)intra / bw_up);
+    for (int e = 0; e < K; ++e) {
+        out_end = out_end + (delay + (double)weight[e] / bw_out);
+        if (redis[e] > 0) {
+            const double start = std::max(out_end, up_free);
+            up_free = start + (delay + (double)redis[e] / bw_up);
+        }
+    }
+    out2[0] = std::max(out_end, up_free);
+    out2[1] = out_end;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -551,6 +710,48 @@ int oracle_synthesize(int S, int G, double bw_up, double bw_out, double delay,
     if (K < 0) return 0;
     cost(S, G, bw_up, bw_out, delay, T.data(), X, io.data(), ii.data(), K, bytes, out4, extra3);
     return 0;
+}
+
+void oracle_redistribution(int S, int G, const int64_t* traffic, int K, const int32_t* stages,
+                           const int64_t* bytes, const int32_t* order, int64_t* offsets,
+                           int64_t* redis_bytes, int n_sel, const int32_t* sel, int64_t* sel_out) {
+    redistribution(S, G, traffic, K, stages, bytes, order, offsets, redis_bytes, n_sel, sel, sel_out);
+}
+
+// Pipelined completion time of a plan.  X, intra_out, intra_in as for oracle_cost;
+// bytes = the K stage rows; order = execution order or NULL; redis = per-stage (indexed
+// by stage, not by position) redistribution bytes, or NULL for the worst case of the
+// Appendix, (G-1) * stage weight.
+void oracle_pipeline_time(int S, int G, double bw_up, double bw_out, double delay, const int64_t* X,
+                          const int64_t* intra_out, const int64_t* intra_in, int K,
+                          const int64_t* bytes, const int32_t* order, const int64_t* redis,
+                          double* out2) {
+    const int N = S * G;
+    i64 bal = 0;
+    for (int a = 0; a < S; ++a)
+        for (int i = 0; i < G; ++i) {
+            i64 handed_off = 0, handed_in = 0;
+            for (int d = 0; d < S; ++d) {
+                if (d == a) continue;
+                for (int k = 0; k < G; ++k) {
+                    if (k == i) continue;
+                    handed_off += at(X, N, a * G + i, d * G + k);
+                    handed_in += at(X, N, a * G + k, d * G + i);
+                }
+            }
+            bal = std::max(bal, std::max(handed_off, handed_in));
+        }
+    i64 intra = 0;
+    for (int g = 0; g < N; ++g) intra = std::max(intra, std::max(intra_out[g], intra_in[g]));
+    std::vector<i64> w(K > 0 ? K : 0), rb(K > 0 ? K : 0);
+    for (int e = 0; e < K; ++e) {
+        const int s = order ? order[e] : e;
+        i64 m = 0;
+        for (int a = 0; a < S; ++a) m = std::max(m, bytes[(size_t)s * S + a]);
+        w[e] = m;
+        rb[e] = redis ? redis[s] : (i64)(G - 1) * m;
+    }
+    pipeline_time(bw_up, bw_out, delay, bal, intra, K, w.data(), rb.data(), out2);
 }
 
 }  // extern "C"

@@ -62,6 +62,13 @@ def _bind(path):
         L.oracle_build_traffic.argtypes = [ctypes.c_int, ctypes.c_int, _i64p, _i32p, ctypes.c_int64,
                                            _i64p]
         L.oracle_build_traffic.restype = ctypes.c_int
+        L.oracle_redistribution.argtypes = [ctypes.c_int, ctypes.c_int, _i64p, ctypes.c_int, _i32p, _i64p,
+                                            _i32p, _i64p, _i64p, ctypes.c_int, _i32p, _i64p]
+        L.oracle_redistribution.restype = None
+        L.oracle_pipeline_time.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double,
+                                           ctypes.c_double, _i64p, _i64p, _i64p, ctypes.c_int, _i64p,
+                                           _i32p, _i64p, _f64p]
+        L.oracle_pipeline_time.restype = None
     return L
 
 
@@ -245,3 +252,48 @@ def stage_order(stage_bytes):
     if K:
         lib().oracle_stage_order(S, K, _p64(by), _p32(order))
     return order[:K]
+
+
+def redistribution(S, G, traffic, stages, stage_bytes, order=None, sel=None):
+    """Plays the stages in execution order (order[e] = e-th stage to run; None = extraction
+    order).  -> (offsets[K,S] int64, redis_bytes[K] int64, matrices[len(sel),S,G,G] int64)"""
+    N = S * G
+    traffic = _c64(traffic).reshape(N, N)
+    st = np.ascontiguousarray(stages, dtype=np.int32).reshape(-1, S)
+    by = _c64(stage_bytes).reshape(-1, S)
+    K = st.shape[0]
+    off = np.zeros((max(K, 1), S), np.int64)
+    rb = np.zeros(max(K, 1), np.int64)
+    sel = np.ascontiguousarray([] if sel is None else sel, dtype=np.int32)
+    n_sel = sel.shape[0]
+    mats = np.zeros((max(n_sel, 1), S, G, G), np.int64)
+    selp = np.ascontiguousarray(sel if n_sel else np.zeros(1, np.int32))
+    if order is not None:
+        order = np.ascontiguousarray(order, dtype=np.int32)
+        assert order.shape[0] == K
+    if K:
+        lib().oracle_redistribution(S, G, _p64(traffic), K, _p32(st), _p64(by),
+                                    _p32(order) if order is not None else None, _p64(off), _p64(rb),
+                                    n_sel, _p32(selp), _p64(mats))
+    return off[:K], rb[:K], mats[:n_sel]
+
+
+def pipeline_time(S, G, bw_up, bw_out, traffic, stage_bytes, order=None, redis=None, delay=0.0):
+    """Overlapped-pipeline completion time of a plan -> [T_pipe, end of the last scale-out].
+    redis: per-stage redistribution bytes (indexed by stage) or None for (G-1) * stage weight."""
+    N = S * G
+    traffic = _c64(traffic).reshape(N, N)
+    _, _, io, ii = aggregate(S, G, traffic)
+    X = rebalance(S, G, traffic)
+    by = _c64(stage_bytes).reshape(-1, S) if len(stage_bytes) else np.zeros((0, S), np.int64)
+    K = by.shape[0]
+    byp = _c64(by if K else np.zeros((1, S), np.int64))
+    if order is not None:
+        order = np.ascontiguousarray(order, dtype=np.int32)
+    if redis is not None:
+        redis = _c64(redis)
+    out2 = np.zeros(2, np.float64)
+    lib().oracle_pipeline_time(S, G, bw_up, bw_out, delay, _p64(X), _p64(io), _p64(ii), K, _p64(byp),
+                               _p32(order) if order is not None and K else None,
+                               _p64(redis) if redis is not None and K else None, _pf(out2))
+    return out2
