@@ -539,14 +539,15 @@ void lane_queues(int G, const i64* tile, std::vector<Queue>* queue) {
         d[k] = std::max<i64>(0, target - r[k]);
         region[k].take(std::min(r[k], target), &(*queue)[k]);   // the head stays on lane k
     }
-    int i = 0, k = 0;                                           // the tails are poured as in rebalance_tile()
-    while (i < G && k < G) {
-        if (s[i] == 0) { ++i; continue; }
-        if (d[k] == 0) { ++k; continue; }
-        const i64 mv = std::min(s[i], d[k]);
-        region[i].take(mv, &(*queue)[k]);
-        s[i] -= mv;
-        d[k] -= mv;
+    // the tails are poured in the order of rebalance_tile(): lowest donor into lowest taker
+    for (int i = 0, k = 0;;) {
+        while (i < G && s[i] == 0) ++i;
+        while (k < G && d[k] == 0) ++k;
+        if (i == G || k == G) break;
+        const i64 piece = std::min(s[i], d[k]);
+        region[i].take(piece, &(*queue)[k]);
+        s[i] -= piece;
+        d[k] -= piece;
     }
 }
 

@@ -13,6 +13,7 @@ import pytest
 import test_oracle_bruteforce as TB
 import test_oracle_build_traffic as TT
 import test_oracle_pins as TP
+import test_oracle_redistribution as TR
 import test_oracle_spreadout as TS
 import test_oracle_stage_order as TO
 
@@ -77,6 +78,28 @@ MUTATIONS = [
     ("traffic construction transposed",
      "traffic[(size_t)src * N + expert_to_gpu[e]] += c * token_bytes;",
      "traffic[(size_t)expert_to_gpu[e] * N + src] += c * token_bytes;"),
+    ("a GPU hands off the head of its region instead of the tail",
+     "region[k].take(std::min(r[k], target), &(*queue)[k]);   // the head stays on lane k",
+     "{ Queue skip; region[k].take(r[k] - std::min(r[k], target), &skip); "
+     "region[k].take(std::min(r[k], target), &(*queue)[k]); region[k] = skip; }"),
+    ("redistribution matrix transposed",
+     "for (const Run& run : got.runs) M[k * G + run.dest] += run.len;",
+     "for (const Run& run : got.runs) M[run.dest * G + k] += run.len;"),
+    ("send offset taken after the stage instead of before",
+     "offsets[(size_t)s * S + a] = sent[(size_t)a * S + d];\n            sent[(size_t)a * S + d] += len;",
+     "sent[(size_t)a * S + d] += len;\n            offsets[(size_t)s * S + a] = sent[(size_t)a * S + d];"),
+    ("bytes that stay on the proxy GPU counted as forwarded",
+     "if (o == g) continue;\n                    fwd += M[g * G + o];",
+     "fwd += M[g * G + o]; if (o == g) continue;"),
+    ("redistribution does not wait for the scale-up fabric",
+     "const double start = std::max(out_end, up_free);",
+     "const double start = out_end;"),
+    ("redistribution does not wait for its own stage",
+     "const double start = std::max(out_end, up_free);",
+     "const double start = up_free;"),
+    ("intra-server portion serialised before the first stage",
+     "double out_end = t, up_free = t;\n    if (intra > 0) up_free = t + (delay + (double)intra / bw_up);",
+     "if (intra > 0) t = t + (delay + (double)intra / bw_up);\n    double out_end = t, up_free = t;"),
 ]
 
 
@@ -103,6 +126,12 @@ def battery(O):
     TO.test_matches_stable_argsort_and_is_a_permutation(O)
     TT.test_identity_and_contiguous_placement(O)
     TT.test_conservation_and_permuted_placement(O)
+    for args in [(3, 2, 9, 1, True), (3, 3, 5, 2, False), (2, 4, 7, 4, True)]:
+        TR.test_against_byte_level_replay(O, *args)
+    TR.test_closed_forms(O)
+    TR.test_pipeline_hand_example(O)
+    TR.test_pipeline_hides_everything_but_the_last_redistribution(O)
+    TR.test_pipeline_scale_up_chain_when_nothing_hides(O)
 
 
 def test_battery_passes_on_the_real_oracle(oracle):
