@@ -176,6 +176,86 @@ int fast_build_traffic_batched(fast_plan_t *plan, int B, int E, const int64_t *t
                                int64_t *out_traffic, int32_t *out_status, hipStream_t stream);
 
 /*
+ * Per-stage send offsets (Section 4.2 Step 2 / Step 3: a server pair's bytes are delivered over
+ * several stages; this says where in each lane's send queue a stage's bytes start).  The stages
+ * are walked in execution order: stage_order[b][e] = e-th stage to run, as written by
+ * fast_stage_order_batched, or NULL for the order in which they were extracted.
+ *   stages, stage_bytes, num_stages  device, as written by fast_synthesize_batched
+ *   out_stage_offset   device, [B][max_stages][S] int64; [b][s][a] = bytes per lane that server a
+ *                      has sent to server stages[b][s][a] in the stages executed before s (0 where
+ *                      a is idle in s); rows s >= K and matrices with negative num_stages are
+ *                      left untouched
+ * Enqueued on `stream`, asynchronous; needs no workspace.
+ */
+int fast_stage_offsets_batched(fast_plan_t *plan, int B, const int32_t *stages,
+                               const int64_t *stage_bytes, const int32_t *num_stages,
+                               const int32_t *stage_order, int64_t *out_stage_offset,
+                               hipStream_t stream);
+
+/*
+ * Exact scale-up volume of every stage's redistribution (Section 4.1 "Redistribution",
+ * Section 4.2 Step 3; the Appendix bounds it by (G-1) * stage weight, the case where all bytes
+ * of a stage are for one GPU).  Which bytes a stage carries follows from this byte-identity
+ * policy (the paper fixes none): the bytes a GPU holds for a server form one region ordered by
+ * destination GPU; balancing keeps the head of the region on the GPU and hands off the tail, cut
+ * into the pieces of out_rebalance in ascending receiver index; a lane sends what its GPU kept,
+ * then the pieces it was handed in ascending donor index; every stage takes the next
+ * stage_bytes[s][a] bytes of each lane's queue.
+ *   traffic, rebalance, stages, stage_bytes, num_stages   device, input and outputs of
+ *                      fast_synthesize_batched for the same B matrices
+ *   stage_order        device, [B][max_stages], or NULL = extraction order
+ *   out_stage_offset   device, [B][max_stages][S], as for fast_stage_offsets_batched
+ *   out_redis_bytes    device, [B][max_stages] int64; [b][s] = largest, over the GPUs of all
+ *                      servers that receive in stage s, of max(bytes the GPU forwards to other
+ *                      GPUs of its server, bytes other GPUs forward to it); entries s >= K are 0
+ * Enqueued on `stream`, asynchronous; uses its own part of the plan's workspace
+ * (20 * S * max_stages + 8 * S * S bytes per matrix).
+ */
+int fast_redistribution_batched(fast_plan_t *plan, int B, const int64_t *traffic,
+                                const int64_t *rebalance, const int32_t *stages,
+                                const int64_t *stage_bytes, const int32_t *num_stages,
+                                const int32_t *stage_order, int64_t *out_stage_offset,
+                                int64_t *out_redis_bytes, hipStream_t stream);
+
+/*
+ * The G x G redistribution matrices of selected stages (same policy and inputs as
+ * fast_redistribution_batched; stage_offset as written by it or by fast_stage_offsets_batched).
+ *   n_sel              number of selected stages (>= 0)
+ *   sel                device, [n_sel][2] int32 = (matrix b, stage s)
+ *   out_matrices       device, [n_sel][S][G][G] int64; [q][d][k][j] = bytes that arrive at server d
+ *                      on lane k (at GPU (d,k)) in stage sel[q] and belong to GPU (d,j); the tile
+ *                      of a server that receives nothing in that stage is zero, and so is every
+ *                      tile of a selection that names no stage (b or s out of range)
+ * Enqueued on `stream`, asynchronous; needs no workspace.
+ */
+int fast_redistribution_matrices(fast_plan_t *plan, int B, const int64_t *traffic,
+                                 const int64_t *rebalance, const int32_t *stages,
+                                 const int64_t *stage_bytes, const int32_t *num_stages,
+                                 const int64_t *stage_offset, int n_sel, const int32_t *sel,
+                                 int64_t *out_matrices, hipStream_t stream);
+
+/*
+ * Completion time of the overlapped pipeline (Section 4.3 "Pipeline structure"): balancing
+ * first; the scale-out stages back to back in execution order; the intra-server portion on the
+ * scale-up fabric alongside the first stage; a stage's redistribution starts when its scale-out
+ * has ended and the scale-up fabric is free (one transfer at a time: the intra-server portion,
+ * then the redistributions in stage order); the last redistribution is exposed.  Each step that
+ * moves bytes costs the wake-up delay plus bytes / bandwidth.
+ * Evaluates the plans of the most recent fast_synthesize_batched call on this plan, which must
+ * have been made with the same B (the balancing and intra-server volumes and the stage weights
+ * are taken from the plan's workspace); FAST_ERR_INVALID_ARG otherwise.
+ *   num_stages         device, [B], as written by that call
+ *   stage_order        device, [B][max_stages], or NULL = extraction order
+ *   redis_bytes        device, [B][max_stages] as written by fast_redistribution_batched, or NULL
+ *                      = the Appendix's worst case (G-1) * stage weight
+ *   out_pipeline_time  device, [B][2] seconds = { completion time, end of the last scale-out
+ *                      stage }; both 0 for a matrix with negative num_stages
+ */
+int fast_pipeline_time_batched(fast_plan_t *plan, int B, const int32_t *num_stages,
+                               const int32_t *stage_order, const int64_t *redis_bytes,
+                               double *out_pipeline_time, hipStream_t stream);
+
+/*
  * Per-kernel timing for measurement.  fast_plan_set_timing(plan, 1) starts a new
  * recording (dropping any earlier one): each following fast_synthesize_batched call,
  * up to FAST_MAX_TIMED_CALLS of them, records HIP events on its stream around its

@@ -23,7 +23,9 @@ FAST_STATUS_INTERNAL = -3
 
 EXPORTS = ("fast_plan_create", "fast_plan_max_stages", "fast_synthesize_batched",
            "fast_plan_set_wakeup_delay", "fast_spreadout_batched", "fast_build_traffic_batched",
-           "fast_stage_order_batched",
+           "fast_stage_order_batched", "fast_stage_offsets_batched",
+           "fast_redistribution_batched", "fast_redistribution_matrices",
+           "fast_pipeline_time_batched",
            "fast_plan_set_timing", "fast_plan_timed_calls", "fast_plan_kernel_ms",
            "fast_plan_destroy")
 
@@ -62,6 +64,15 @@ def lib():
         L.fast_build_traffic_batched.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, vp,
                                                  ctypes.c_int64, vp, vp, vp]
         L.fast_build_traffic_batched.restype = ctypes.c_int
+        L.fast_stage_offsets_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp]
+        L.fast_stage_offsets_batched.restype = ctypes.c_int
+        L.fast_redistribution_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.fast_redistribution_batched.restype = ctypes.c_int
+        L.fast_redistribution_matrices.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp,
+                                                   ctypes.c_int, vp, vp, vp]
+        L.fast_redistribution_matrices.restype = ctypes.c_int
+        L.fast_pipeline_time_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp]
+        L.fast_pipeline_time_batched.restype = ctypes.c_int
         L.fast_plan_set_timing.argtypes = [vp, ctypes.c_int]
         L.fast_plan_set_timing.restype = ctypes.c_int
         L.fast_plan_timed_calls.argtypes = [vp]
@@ -125,8 +136,45 @@ def fast_build_traffic_batched(plan, B, E, tokens_per_expert, expert_to_gpu, tok
     rc = lib().fast_build_traffic_batched(plan, int(B), int(E), tokens_per_expert, expert_to_gpu,
                                           int(token_bytes), out_traffic, out_status, stream)
     if rc != FAST_OK:
-        raise FastError("fast_build_traffic_batched",
-           "fast_stage_order_batched", rc)
+        raise FastError("fast_build_traffic_batched", rc)
+
+
+def fast_stage_offsets_batched(plan, B, stages, stage_bytes, num_stages, stage_order,
+                               out_stage_offset, stream):
+    """Raw call: buffer arguments are device addresses (int; stage_order may be None)."""
+    rc = lib().fast_stage_offsets_batched(plan, int(B), stages, stage_bytes, num_stages, stage_order,
+                                          out_stage_offset, stream)
+    if rc != FAST_OK:
+        raise FastError("fast_stage_offsets_batched", rc)
+
+
+def fast_redistribution_batched(plan, B, traffic, rebalance, stages, stage_bytes, num_stages,
+                                stage_order, out_stage_offset, out_redis_bytes, stream):
+    """Raw call: buffer arguments are device addresses (int; stage_order may be None)."""
+    rc = lib().fast_redistribution_batched(plan, int(B), traffic, rebalance, stages, stage_bytes,
+                                           num_stages, stage_order, out_stage_offset,
+                                           out_redis_bytes, stream)
+    if rc != FAST_OK:
+        raise FastError("fast_redistribution_batched", rc)
+
+
+def fast_redistribution_matrices(plan, B, traffic, rebalance, stages, stage_bytes, num_stages,
+                                 stage_offset, n_sel, sel, out_matrices, stream):
+    """Raw call: buffer arguments are device addresses (int)."""
+    rc = lib().fast_redistribution_matrices(plan, int(B), traffic, rebalance, stages, stage_bytes,
+                                            num_stages, stage_offset, int(n_sel), sel, out_matrices,
+                                            stream)
+    if rc != FAST_OK:
+        raise FastError("fast_redistribution_matrices", rc)
+
+
+def fast_pipeline_time_batched(plan, B, num_stages, stage_order, redis_bytes, out_pipeline_time,
+                               stream):
+    """Raw call: buffer arguments are device addresses (int; stage_order, redis_bytes may be None)."""
+    rc = lib().fast_pipeline_time_batched(plan, int(B), num_stages, stage_order, redis_bytes,
+                                          out_pipeline_time, stream)
+    if rc != FAST_OK:
+        raise FastError("fast_pipeline_time_batched", rc)
 
 
 def fast_plan_set_timing(plan, enable):
@@ -228,6 +276,66 @@ class Synthesizer:
             fast_stage_order_batched(self.plan, B, out.stage_bytes.data_ptr(),
                                      out.num_stages.data_ptr(), order.data_ptr(), stream)
         return order
+
+    def _stream(self):
+        import torch
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def stage_offsets(self, out, order=None):
+        """Per-stage send offsets of the plans in `out`, stages walked in `order` (tensor from
+        stage_order(), or None = extraction order) -> int64 tensor [B, max_stages, S]."""
+        import torch
+        B = out.num_stages.shape[0]
+        off = torch.zeros((B, self.max_stages, self.S), dtype=torch.int64, device=self.device)
+        with torch.cuda.device(self.device):
+            fast_stage_offsets_batched(self.plan, B, out.stages.data_ptr(), out.stage_bytes.data_ptr(),
+                                       out.num_stages.data_ptr(),
+                                       order.data_ptr() if order is not None else None,
+                                       off.data_ptr(), self._stream())
+        return off
+
+    def redistribution(self, traffic, out, order=None):
+        """Exact scale-up volume of every stage's redistribution -> (stage_offset int64
+        [B, max_stages, S], redis_bytes int64 [B, max_stages])."""
+        import torch
+        B = out.num_stages.shape[0]
+        off = torch.zeros((B, self.max_stages, self.S), dtype=torch.int64, device=self.device)
+        rb = torch.empty((B, self.max_stages), dtype=torch.int64, device=self.device)
+        with torch.cuda.device(self.device):
+            fast_redistribution_batched(self.plan, B, traffic.data_ptr(), out.rebalance.data_ptr(),
+                                        out.stages.data_ptr(), out.stage_bytes.data_ptr(),
+                                        out.num_stages.data_ptr(),
+                                        order.data_ptr() if order is not None else None,
+                                        off.data_ptr(), rb.data_ptr(), self._stream())
+        return off, rb
+
+    def redistribution_matrices(self, traffic, out, stage_offset, sel):
+        """sel: int32 tensor [n, 2] of (matrix, stage) -> int64 tensor [n, S, G, G]."""
+        import torch
+        if sel.dtype != torch.int32 or sel.dim() != 2 or sel.shape[1] != 2 or not sel.is_contiguous():
+            raise ValueError("sel must be a contiguous int32 tensor [n, 2]")
+        B = out.num_stages.shape[0]
+        n = sel.shape[0]
+        mats = torch.empty((n, self.S, self.G, self.G), dtype=torch.int64, device=self.device)
+        with torch.cuda.device(self.device):
+            fast_redistribution_matrices(self.plan, B, traffic.data_ptr(), out.rebalance.data_ptr(),
+                                         out.stages.data_ptr(), out.stage_bytes.data_ptr(),
+                                         out.num_stages.data_ptr(), stage_offset.data_ptr(), n,
+                                         sel.data_ptr(), mats.data_ptr(), self._stream())
+        return mats
+
+    def pipeline_time(self, out, order=None, redis_bytes=None):
+        """Overlapped-pipeline completion time of the plans of the last synthesize() call
+        -> float64 tensor [B, 2] (completion time, end of the last scale-out stage)."""
+        import torch
+        B = out.num_stages.shape[0]
+        t = torch.empty((B, 2), dtype=torch.float64, device=self.device)
+        with torch.cuda.device(self.device):
+            fast_pipeline_time_batched(self.plan, B, out.num_stages.data_ptr(),
+                                       order.data_ptr() if order is not None else None,
+                                       redis_bytes.data_ptr() if redis_bytes is not None else None,
+                                       t.data_ptr(), self._stream())
+        return t
 
     def build_traffic(self, tokens_per_expert, expert_to_gpu, token_bytes):
         """counts int64 [B, N, E], placement int32 [B, E] -> (traffic int64 [B, N, N], status

@@ -1,5 +1,5 @@
 // Host side of the C ABI declared in include/fast.h: argument checks, the plan's
-// device workspace, and the three kernel launches of one synthesis call.
+// device workspaces, and the kernel launches of every entry point.
 #include "fast.h"
 
 #include <hip/hip_runtime.h>
@@ -14,6 +14,8 @@
 #include "k4_spreadout.hpp"
 #include "k5_build_traffic.hpp"
 #include "k6_stage_order.hpp"
+#include "k7_redistribution.hpp"
+#include "k8_pipeline.hpp"
 
 using fastk::i64;
 
@@ -38,6 +40,14 @@ struct fast_plan {
     int so_cap_B;
     fastk::u64* soKeys;    // [B][P]
     int32_t* soIdx;        // [B][P]
+    // workspace of the redistribution analysis for `rd_cap_B` matrices
+    int rd_cap_B;
+    int32_t* rdStart;      // [B][S][S] start of the pair's list within its source server's row
+    int32_t* rdCnt;        // [B][S][S] stages in which the pair occurs
+    int32_t* rdListS;      // [B][S][max_stages] stage index
+    i64* rdListOff;        // [B][S][max_stages] send offset
+    i64* rdListLen;        // [B][S][max_stages] bytes per lane
+    int last_B;            // B of the most recent synthesis call (0 = none)
     // timing: four events per recorded call
     int timing;
     int n_timed;
@@ -174,6 +184,10 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     p->so_cap_B = 0;
     p->soKeys = nullptr;
     p->soIdx = nullptr;
+    p->rd_cap_B = 0;
+    p->rdStart = p->rdCnt = p->rdListS = nullptr;
+    p->rdListOff = p->rdListLen = nullptr;
+    p->last_B = 0;
     p->timing = 0;
     p->n_timed = 0;
     p->ev = nullptr;
@@ -192,6 +206,15 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::k3_cost),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)(next_pow2(p->max_stages) * sizeof(i64)));
+    if (e == hipSuccess && fastk::rd_offsets_lds_bytes(S, true) > 48 * 1024) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::rd_offsets<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)fastk::rd_offsets_lds_bytes(S, true));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::rd_offsets<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)fastk::rd_offsets_lds_bytes(S, false));
+    }
     if (e != hipSuccess) {
         (void)hipGetLastError();
         delete p;
@@ -267,6 +290,7 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
         ++p->n_timed;
     }
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
+    p->last_B = B;
     return FAST_OK;
 }
 
@@ -360,6 +384,112 @@ int fast_build_traffic_batched(fast_plan_t* p, int B, int E, const int64_t* toke
     return FAST_OK;
 }
 
+int fast_stage_offsets_batched(fast_plan_t* p, int B, const int32_t* stages,
+                               const int64_t* stage_bytes, const int32_t* num_stages,
+                               const int32_t* stage_order, int64_t* out_stage_offset,
+                               hipStream_t stream) {
+    if (!p || B < 0) return FAST_ERR_INVALID_ARG;
+    if (B == 0) return FAST_OK;
+    if (!stages || !stage_bytes || !num_stages || !out_stage_offset) return FAST_ERR_INVALID_ARG;
+    if (B > 65535) return FAST_ERR_UNSUPPORTED;
+    const dim3 grid((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS, B);
+    hipLaunchKernelGGL((fastk::rd_offsets<false>), grid, dim3(fastk::RD_ROWS),
+                       fastk::rd_offsets_lds_bytes(p->S, false), stream, stages,
+                       reinterpret_cast<const i64*>(stage_bytes), num_stages, stage_order,
+                       reinterpret_cast<i64*>(out_stage_offset), nullptr, nullptr, nullptr, nullptr,
+                       nullptr, p->S, p->max_stages);
+    if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
+    return FAST_OK;
+}
+
+int fast_redistribution_batched(fast_plan_t* p, int B, const int64_t* traffic,
+                                const int64_t* rebalance, const int32_t* stages,
+                                const int64_t* stage_bytes, const int32_t* num_stages,
+                                const int32_t* stage_order, int64_t* out_stage_offset,
+                                int64_t* out_redis_bytes, hipStream_t stream) {
+    if (!p || B < 0) return FAST_ERR_INVALID_ARG;
+    if (B == 0) return FAST_OK;
+    if (!traffic || !rebalance || !stages || !stage_bytes || !num_stages || !out_stage_offset ||
+        !out_redis_bytes)
+        return FAST_ERR_INVALID_ARG;
+    if (B > 65535) return FAST_ERR_UNSUPPORTED;
+    const size_t S = p->S, M = p->max_stages;
+    if (B > p->rd_cap_B) {
+        if (p->rdListOff) (void)hipFree(p->rdListOff);
+        p->rdListOff = nullptr;
+        p->rd_cap_B = 0;
+        const size_t nPair = (size_t)B * S * S, nList = (size_t)B * S * M;
+        unsigned char* base = nullptr;
+        if (hipMalloc(&base, nList * (2 * sizeof(i64) + sizeof(int32_t)) +
+                                 2 * nPair * sizeof(int32_t)) != hipSuccess) {
+            (void)hipGetLastError();
+            return FAST_ERR_OOM;
+        }
+        // 8-byte arrays first so that every array is naturally aligned
+        p->rdListOff = reinterpret_cast<i64*>(base);
+        p->rdListLen = p->rdListOff + nList;
+        p->rdListS = reinterpret_cast<int32_t*>(p->rdListLen + nList);
+        p->rdStart = p->rdListS + nList;
+        p->rdCnt = p->rdStart + nPair;
+        p->rd_cap_B = B;
+    }
+    const size_t nR = (size_t)B * M;
+    fastk::u64* redis = reinterpret_cast<fastk::u64*>(out_redis_bytes);
+    hipLaunchKernelGGL(fastk::rd_zero, dim3((unsigned)((nR + 255) / 256 < 2048 ? (nR + 255) / 256
+                                                                              : 2048)),
+                       dim3(256), 0, stream, redis, nR);
+    const dim3 grid((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS, B);
+    hipLaunchKernelGGL((fastk::rd_offsets<true>), grid, dim3(fastk::RD_ROWS),
+                       fastk::rd_offsets_lds_bytes(p->S, true), stream, stages,
+                       reinterpret_cast<const i64*>(stage_bytes), num_stages, stage_order,
+                       reinterpret_cast<i64*>(out_stage_offset), p->rdStart, p->rdCnt, p->rdListS,
+                       p->rdListOff, p->rdListLen, p->S, p->max_stages);
+    hipLaunchKernelGGL(fastk::rd_volumes, dim3(p->S * p->S, B), dim3(64), 0, stream,
+                       reinterpret_cast<const i64*>(traffic), reinterpret_cast<const i64*>(rebalance),
+                       num_stages, p->rdStart, p->rdCnt, p->rdListS, p->rdListOff, p->rdListLen,
+                       redis, p->S, p->G, p->max_stages);
+    if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
+    return FAST_OK;
+}
+
+int fast_redistribution_matrices(fast_plan_t* p, int B, const int64_t* traffic,
+                                 const int64_t* rebalance, const int32_t* stages,
+                                 const int64_t* stage_bytes, const int32_t* num_stages,
+                                 const int64_t* stage_offset, int n_sel, const int32_t* sel,
+                                 int64_t* out_matrices, hipStream_t stream) {
+    if (!p || B < 0 || n_sel < 0) return FAST_ERR_INVALID_ARG;
+    if (B == 0 || n_sel == 0) return FAST_OK;
+    if (!traffic || !rebalance || !stages || !stage_bytes || !num_stages || !stage_offset || !sel ||
+        !out_matrices)
+        return FAST_ERR_INVALID_ARG;
+    if (n_sel > 65535) return FAST_ERR_UNSUPPORTED;     // grid.y limit
+    const size_t n = (size_t)n_sel * p->S * p->G * p->G;
+    hipLaunchKernelGGL(fastk::rd_zero, dim3((unsigned)((n + 255) / 256 < 2048 ? (n + 255) / 256
+                                                                            : 2048)),
+                       dim3(256), 0, stream, reinterpret_cast<fastk::u64*>(out_matrices), n);
+    hipLaunchKernelGGL(fastk::rd_matrices, dim3(p->S, n_sel), dim3(64), 0, stream,
+                       reinterpret_cast<const i64*>(traffic), reinterpret_cast<const i64*>(rebalance),
+                       stages, reinterpret_cast<const i64*>(stage_bytes),
+                       reinterpret_cast<const i64*>(stage_offset), num_stages, sel,
+                       reinterpret_cast<i64*>(out_matrices), B, p->S, p->G, p->max_stages);
+    if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
+    return FAST_OK;
+}
+
+int fast_pipeline_time_batched(fast_plan_t* p, int B, const int32_t* num_stages,
+                               const int32_t* stage_order, const int64_t* redis_bytes,
+                               double* out_pipeline_time, hipStream_t stream) {
+    if (!p || B < 0) return FAST_ERR_INVALID_ARG;
+    if (B == 0) return FAST_OK;
+    if (!num_stages || !out_pipeline_time) return FAST_ERR_INVALID_ARG;
+    if (B != p->last_B) return FAST_ERR_INVALID_ARG;    // no synthesis call of this size to evaluate
+    hipLaunchKernelGGL(fastk::pl_time, dim3(B), dim3(fastk::PL_THREADS), 0, stream, p->wsPart,
+                       p->wsC, num_stages, stage_order, reinterpret_cast<const i64*>(redis_bytes),
+                       out_pipeline_time, p->S, p->G, p->max_stages, p->bw_up, p->bw_out, p->delay);
+    if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
+    return FAST_OK;
+}
+
 int fast_plan_set_timing(fast_plan_t* p, int enable) {
     if (!p) return FAST_ERR_INVALID_ARG;
     p->timing = enable ? 1 : 0;
@@ -389,6 +519,7 @@ void fast_plan_destroy(fast_plan_t* p) {
     free_workspace(p);
     free_spo_workspace(p);
     if (p->soKeys) (void)hipFree(p->soKeys);
+    if (p->rdListOff) (void)hipFree(p->rdListOff);
     if (p->ev) {
         for (int c = 0; c < FAST_MAX_TIMED_CALLS; ++c)
             for (int k = 0; k < 4; ++k)
