@@ -15,6 +15,8 @@ quoted on.  Prints ONE JSON line:
   cpu_baseline   the CPU oracle timed on this machine's host cores on a bounded sample
   latency_b1     the same configuration at B = 1 (true single-matrix latency)
   spreadout_baseline  time of the SpreadOut comparison pass and predicted-time ratios
+  pipeline_analysis   time of stage order + exact redistribution volumes + pipelined completion
+                      time of the same plans, and how they compare with the serial model
 """
 import argparse
 import json
@@ -180,6 +182,35 @@ def main():
            "mean_T_spreadout_gpu_over_t_opt": float((sp[:, 0] / tp[:, 3]).mean()),
            "mean_T_spreadout_server_over_t_opt": float((sp[:, 1] / tp[:, 3]).mean())}
 
+    # Redistribution analysis and pipelined completion time of the same plans (stage order ->
+    # send offsets + exact scale-up volume per stage -> overlapped-pipeline time)
+    def timed(fn, reps):
+        r = fn()
+        torch.cuda.synchronize()
+        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            r = fn()
+        b_.record()
+        torch.cuda.synchronize()
+        return r, a.elapsed_time(b_) / reps
+    nrd = max(2, min(args.steps, 5))
+    order, order_ms = timed(lambda: syn.stage_order(out), nrd)
+    (soff, rbytes), redis_ms = timed(lambda: syn.redistribution(traffic, out, order), nrd)
+    pw, pipe_ms = timed(lambda: syn.pipeline_time(out, order), nrd)
+    pe, _ = timed(lambda: syn.pipeline_time(out, order, rbytes), 1)
+    pwh, peh = pw.cpu().numpy(), pe.cpu().numpy()
+    by_max = out.stage_bytes.amax(dim=2)
+    kmask = torch.arange(syn.max_stages, device=dev)[None, :] < out.num_stages[:, None]
+    worst = (G - 1) * by_max[kmask].double().sum().item()
+    exact = rbytes[kmask].double().sum().item()
+    del soff
+    pipe = {"stage_order_ms": order_ms, "redistribution_ms": redis_ms, "pipeline_time_ms": pipe_ms,
+            "stage_pairs": int((out.stages >= 0)[kmask].sum().item()),
+            "mean_T_pipeline_worstcase_over_t_opt": float((pwh[:, 0] / tp[:, 3]).mean()),
+            "mean_T_pipeline_exact_over_t_opt": float((peh[:, 0] / tp[:, 3]).mean()),
+            "exact_over_worstcase_redistribution_bytes": exact / worst if worst else None}
+
     cpu = None
     if not args.no_cpu:
         host = traffic[:32].cpu().numpy()
@@ -216,6 +247,7 @@ def main():
         "end_to_end_GBs": (k1_bytes + k2_bytes + k3_bytes) / (ms_per_step * 1e-3) / 1e9,
         "latency_b1": lat,
         "spreadout_baseline": spo,
+        "pipeline_analysis": pipe,
         "cpu_baseline": cpu,
     }
     syn.close()

@@ -207,13 +207,13 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)(next_pow2(p->max_stages) * sizeof(i64)));
     if (e == hipSuccess && fastk::rd_offsets_lds_bytes(S, true) > 48 * 1024) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::rd_offsets<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)fastk::rd_offsets_lds_bytes(S, true));
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::rd_offsets<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)fastk::rd_offsets_lds_bytes(S, false));
+        const void* kern[4] = {reinterpret_cast<const void*>(&fastk::rd_offsets<true, true>),
+                               reinterpret_cast<const void*>(&fastk::rd_offsets<true, false>),
+                               reinterpret_cast<const void*>(&fastk::rd_offsets<false, true>),
+                               reinterpret_cast<const void*>(&fastk::rd_offsets<false, false>)};
+        for (int k = 0; k < 4 && e == hipSuccess; ++k)
+            e = hipFuncSetAttribute(kern[k], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)fastk::rd_offsets_lds_bytes(S, k < 2));
     }
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -393,11 +393,11 @@ int fast_stage_offsets_batched(fast_plan_t* p, int B, const int32_t* stages,
     if (!stages || !stage_bytes || !num_stages || !out_stage_offset) return FAST_ERR_INVALID_ARG;
     if (B > 65535) return FAST_ERR_UNSUPPORTED;
     const dim3 grid((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS, B);
-    hipLaunchKernelGGL((fastk::rd_offsets<false>), grid, dim3(fastk::RD_ROWS),
-                       fastk::rd_offsets_lds_bytes(p->S, false), stream, stages,
-                       reinterpret_cast<const i64*>(stage_bytes), num_stages, stage_order,
-                       reinterpret_cast<i64*>(out_stage_offset), nullptr, nullptr, nullptr, nullptr,
-                       nullptr, p->S, p->max_stages);
+    auto kern = stage_order ? &fastk::rd_offsets<false, true> : &fastk::rd_offsets<false, false>;
+    hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S, false),
+                       stream, stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
+                       stage_order, reinterpret_cast<i64*>(out_stage_offset), nullptr, nullptr,
+                       nullptr, nullptr, nullptr, p->S, p->max_stages);
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     return FAST_OK;
 }
@@ -439,11 +439,11 @@ int fast_redistribution_batched(fast_plan_t* p, int B, const int64_t* traffic,
                                                                               : 2048)),
                        dim3(256), 0, stream, redis, nR);
     const dim3 grid((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS, B);
-    hipLaunchKernelGGL((fastk::rd_offsets<true>), grid, dim3(fastk::RD_ROWS),
-                       fastk::rd_offsets_lds_bytes(p->S, true), stream, stages,
-                       reinterpret_cast<const i64*>(stage_bytes), num_stages, stage_order,
-                       reinterpret_cast<i64*>(out_stage_offset), p->rdStart, p->rdCnt, p->rdListS,
-                       p->rdListOff, p->rdListLen, p->S, p->max_stages);
+    auto kern = stage_order ? &fastk::rd_offsets<true, true> : &fastk::rd_offsets<true, false>;
+    hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S, true),
+                       stream, stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
+                       stage_order, reinterpret_cast<i64*>(out_stage_offset), p->rdStart, p->rdCnt,
+                       p->rdListS, p->rdListOff, p->rdListLen, p->S, p->max_stages);
     hipLaunchKernelGGL(fastk::rd_volumes, dim3(p->S * p->S, B), dim3(64), 0, stream,
                        reinterpret_cast<const i64*>(traffic), reinterpret_cast<const i64*>(rebalance),
                        num_stages, p->rdStart, p->rdCnt, p->rdListS, p->rdListOff, p->rdListLen,

@@ -41,7 +41,7 @@
 namespace fastk {
 
 constexpr int RD_ROWS = 64;     // source servers per workgroup of rd_offsets (one wavefront)
-constexpr int RD_UNROLL = 8;    // stages whose loads are in flight together
+constexpr int RD_UNROLL = 16;   // stages per batch of the pipelined walk
 
 inline size_t rd_offsets_lds_bytes(int S, bool lists) {
     return (size_t)RD_ROWS * S * (lists ? sizeof(i64) + sizeof(int32_t) : sizeof(i64));
@@ -55,7 +55,11 @@ __global__ void __launch_bounds__(256) rd_zero(u64* __restrict__ p, size_t n) {
 
 // grid (ceil(S / RD_ROWS), B), RD_ROWS threads.  Lane l owns source server a and the
 // LDS column [*][l]; no two lanes share a word, so the kernel needs no barrier.
-template <bool LISTS>
+// The walk over the stages is a chain of dependent steps (stage index -> the stage's
+// row -> the running offset in LDS), so it is software-pipelined by hand: while batch n
+// of RD_UNROLL stages is processed, the rows of batch n+1 and the indices of batch n+2
+// are in flight.
+template <bool LISTS, bool ORDERED>
 __global__ void __launch_bounds__(RD_ROWS)
 rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_bytes,
            const int32_t* __restrict__ num_stages, const int32_t* __restrict__ order,
@@ -63,6 +67,7 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
            int32_t* __restrict__ list_s, i64* __restrict__ list_off, i64* __restrict__ list_len,
            int S, int max_stages) {
     extern __shared__ __align__(16) unsigned char rd_smem[];
+    constexpr int U = RD_UNROLL;
     const int b = blockIdx.y;
     const int lane = threadIdx.x;
     const int a = blockIdx.x * RD_ROWS + lane;
@@ -78,19 +83,19 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
     }
     const int32_t* st = stages + (size_t)b * max_stages * S;
     const i64* by = stage_bytes + (size_t)b * max_stages * S;
-    const int32_t* ord = order ? order + (size_t)b * max_stages : nullptr;
+    const int32_t* ord = ORDERED ? order + (size_t)b * max_stages : nullptr;
     i64* off_out = out_offset + (size_t)b * max_stages * S;
 
     if constexpr (LISTS) {
         // how often does a send to each d, then where does each pair's list start
-        for (int s0 = 0; s0 < K; s0 += RD_UNROLL) {
-            int dd[RD_UNROLL];
+        for (int s0 = 0; s0 < K; s0 += 2 * U) {
+            int dd[2 * U];
 #pragma unroll
-            for (int u = 0; u < RD_UNROLL; ++u)
+            for (int u = 0; u < 2 * U; ++u)
                 dd[u] = s0 + u < K ? st[(size_t)(s0 + u) * S + ac] : -1;
 #pragma unroll
-            for (int u = 0; u < RD_UNROLL; ++u)
-                if (live && dd[u] >= 0 && dd[u] < S) next[dd[u] * RD_ROWS + lane] += 1;
+            for (int u = 0; u < 2 * U; ++u)
+                if (dd[u] >= 0 && dd[u] < S) atomicAdd(&next[dd[u] * RD_ROWS + lane], 1);
         }
         if (live) {
             int acc = 0;
@@ -105,38 +110,73 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
     }
 
     const size_t lbase = ((size_t)b * S + ac) * max_stages;
-    for (int e0 = 0; e0 < K; e0 += RD_UNROLL) {
-        int ss[RD_UNROLL], dd[RD_UNROLL];
-        i64 ln[RD_UNROLL];
-#pragma unroll
-        for (int u = 0; u < RD_UNROLL; ++u) {
-            int s = -1;
-            if (e0 + u < K) s = ord ? ord[e0 + u] : e0 + u;
-            if (s < 0 || s >= K) s = -1;                            // not a stage: skipped
-            ss[u] = s;
-            dd[u] = s >= 0 ? st[(size_t)s * S + ac] : -1;
-            ln[u] = s >= 0 ? by[(size_t)s * S + ac] : 0;
-        }
-#pragma unroll
-        for (int u = 0; u < RD_UNROLL; ++u) {
-            if (!live || ss[u] < 0) continue;
-            const int d = dd[u];
-            i64 off = 0;
-            if (d >= 0 && d < S) {
-                off = sent[d * RD_ROWS + lane];
-                sent[d * RD_ROWS + lane] = off + ln[u];
-                if constexpr (LISTS) {
-                    const int pos = next[d * RD_ROWS + lane];
-                    next[d * RD_ROWS + lane] = pos + 1;
-                    if (pos < max_stages) {     // always true for a well-formed stage order
-                        list_s[lbase + pos] = ss[u];
-                        list_off[lbase + pos] = off;
-                        list_len[lbase + pos] = ln[u];
-                    }
-                }
+    // one stage: running offset of the pair (a, d) in LDS, optional list entry, send offset out.
+    // Branch-free for an idle row (d < 0): it adds 0 to word 0 of the lane's column.  Lanes
+    // beyond S work on a copy of row S-1 in their own LDS column and store nothing.
+    auto stage = [&](int s, int d, i64 len) {
+        const bool sends = d >= 0 && d < S;
+        const int w = (sends ? d : 0) * RD_ROWS + lane;
+        // fetch-and-add in one LDS instruction: the adds of a batch queue up in the LDS pipe
+        // in program order instead of each waiting for the previous read to come back
+        const i64 before = (i64)atomicAdd(reinterpret_cast<u64*>(&sent[w]), (u64)(sends ? len : 0));
+        const i64 off = sends ? before : 0;
+        if constexpr (LISTS) {
+            const int pos = atomicAdd(&next[w], sends ? 1 : 0);
+            if (live && sends && pos < max_stages) {    // pos < max_stages for any permutation
+                list_s[lbase + pos] = s;
+                list_off[lbase + pos] = off;
+                list_len[lbase + pos] = len;
             }
-            off_out[(size_t)ss[u] * S + a] = off;
         }
+        if (live) off_out[(size_t)s * S + a] = off;
+    };
+    // Stage indices of the batch at position e0: lane u holds the u-th (one coalesced load),
+    // v_readlane hands them out as scalars.  An entry that is no stage index is clamped.
+    auto load_idx = [&](int e0) -> int {
+        if constexpr (ORDERED) return ord[e0 + (lane & (U - 1))];
+        return e0 + (lane & (U - 1));
+    };
+    auto stage_of = [&](int iv, int u) -> int {
+        const int s = __builtin_amdgcn_readlane(iv, u);
+        return s < 0 ? 0 : (s >= K ? K - 1 : s);
+    };
+    auto load_rows = [&](int iv, int (&ss)[U], int (&dd)[U], i64 (&ln)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            ss[u] = stage_of(iv, u);
+            dd[u] = st[(size_t)ss[u] * S + ac];
+            ln[u] = by[(size_t)ss[u] * S + ac];
+        }
+    };
+    auto process = [&](const int (&ss)[U], const int (&dd)[U], const i64 (&ln)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) stage(ss[u], dd[u], ln[u]);
+    };
+    // Three batch buffers take the roles "being processed", "rows in flight", "indices in
+    // flight" in turn, so no register is copied while its load is outstanding.
+    const int nb = K / U;                       // full batches; the tail follows below
+    int i0 = 0, i1 = 0, i2 = 0;
+    int s0[U], s1[U], s2[U], d0[U], d1[U], d2[U];
+    i64 l0[U], l1[U], l2[U];
+    if (nb > 0) { i0 = load_idx(0); load_rows(i0, s0, d0, l0); }
+    if (nb > 1) i1 = load_idx(U);
+    for (int n = 0; n < nb; n += 3) {
+        if (n + 1 < nb) load_rows(i1, s1, d1, l1);
+        if (n + 2 < nb) i2 = load_idx((n + 2) * U);
+        process(s0, d0, l0);
+        if (n + 1 >= nb) break;
+        if (n + 2 < nb) load_rows(i2, s2, d2, l2);
+        if (n + 3 < nb) i0 = load_idx((n + 3) * U);
+        process(s1, d1, l1);
+        if (n + 2 >= nb) break;
+        if (n + 3 < nb) load_rows(i0, s0, d0, l0);
+        if (n + 4 < nb) i1 = load_idx((n + 4) * U);
+        process(s2, d2, l2);
+    }
+    for (int e = nb * U; e < K; ++e) {
+        int s = ORDERED ? ord[e] : e;
+        s = s < 0 ? 0 : (s >= K ? K - 1 : s);
+        stage(s, st[(size_t)s * S + ac], by[(size_t)s * S + ac]);
     }
 }
 
