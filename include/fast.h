@@ -185,6 +185,8 @@ int fast_build_traffic_batched(fast_plan_t *plan, int B, int E, const int64_t *t
  *                      has sent to server stages[b][s][a] in the stages executed before s (0 where
  *                      a is idle in s); rows s >= K and matrices with negative num_stages are
  *                      left untouched
+ * stage_order[b][0..K) has to be a permutation of 0..K-1; entries outside that range are clamped
+ * into it (no out-of-bounds access), and the offsets of such a matrix are unspecified.
  * Enqueued on `stream`, asynchronous; needs no workspace.
  */
 int fast_stage_offsets_batched(fast_plan_t *plan, int B, const int32_t *stages,
