@@ -143,6 +143,16 @@ void launch_k1(const fast_plan* p, int B, const i64* traffic, i64* X, hipStream_
                        p->wsT, p->wsQ, p->wsPart, p->S);
 }
 
+// The decomposition kernel for S servers: one or two rows per lane, and the variant without
+// bounds predicates when S fills the wavefront exactly.
+typedef void (*k2_fn)(const i64*, const i64*, int32_t*, i64*, int32_t*, i64*, int, int);
+k2_fn k2_kernel(int S) {
+    if (S == 128) return &fastk::k2_birkhoff<2, true>;
+    if (S > 64) return &fastk::k2_birkhoff<2, false>;
+    if (S == 64) return &fastk::k2_birkhoff<1, true>;
+    return &fastk::k2_birkhoff<1, false>;
+}
+
 int next_pow2(int v) {
     int n = 1;
     while (n < v) n <<= 1;
@@ -196,11 +206,8 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     // CU's 160 KiB, which has to be requested explicitly above 64 KiB.
     const int lds2 = (int)fastk::k2_lds_bytes(S);
     hipError_t e = hipSuccess;
-    if (S > 64)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::k2_birkhoff<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds2);
-    else if (lds2 > 48 * 1024)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::k2_birkhoff<1>),
+    if (lds2 > 48 * 1024)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2_kernel(S)),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds2);
     if (e == hipSuccess && link_bw_up < (double)(G - 1) * link_bw_out)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::k3_cost),
@@ -269,14 +276,9 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
 
     const size_t lds2 = fastk::k2_lds_bytes(p->S);
     i64* sb = reinterpret_cast<i64*>(out_stage_bytes);
-    if (p->S > 64)
-        hipLaunchKernelGGL((fastk::k2_birkhoff<2>), dim3(B), dim3(fastk::K2_THREADS), lds2, stream,
-                           p->wsQ, p->wsPart, out_stages, sb, out_num_stages, p->wsC, p->S,
-                           p->max_stages);
-    else
-        hipLaunchKernelGGL((fastk::k2_birkhoff<1>), dim3(B), dim3(fastk::K2_THREADS), lds2, stream,
-                           p->wsQ, p->wsPart, out_stages, sb, out_num_stages, p->wsC, p->S,
-                           p->max_stages);
+    hipLaunchKernelGGL(k2_kernel(p->S), dim3(B), dim3(fastk::K2_THREADS),
+                       lds2, stream, p->wsQ, p->wsPart, out_stages, sb, out_num_stages, p->wsC, p->S,
+                       p->max_stages);
     if (ev) (void)hipEventRecord(ev[2], stream);
 
     const bool slow_up = p->bw_up < (double)(p->G - 1) * p->bw_out;

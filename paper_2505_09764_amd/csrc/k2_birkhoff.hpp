@@ -124,7 +124,9 @@ __device__ __forceinline__ i64 wave_scan_incl(i64 v, int lane) {
 }
 
 // NR = rows (and columns) per lane: 1 for S <= 64, 2 for S <= 128.
-template <int NR>
+// NR: rows and columns per lane; FULL: S == 64 * NR, every lane slot holds a real row (the
+// stage rows are then stored without a per-lane bounds predicate).
+template <int NR, bool FULL>
 __global__ void __launch_bounds__(K2_THREADS)
 k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             int32_t* __restrict__ out_stages, i64* __restrict__ out_bytes,
@@ -495,7 +497,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             const i64 real = c < rl[k] ? c : rl[k];
             rl[k] -= real;
             rv[k] -= c;
-            if (lid[k] < S) {
+            if (FULL || lid[k] < S) {
                 srow[lid[k]] = real > 0 ? mr[k] : -1;
                 brow[lid[k]] = real;
             }
