@@ -42,6 +42,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <limits>
 #include <type_traits>
 
 #include "k1_rebalance.hpp"
@@ -239,114 +240,267 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         }
     }
 
-    int lid[NR];
-    u32 rowbase[NR];
-#pragma unroll
-    for (int k = 0; k < NR; ++k) {
-        lid[k] = lane + 64 * k;
-        rowbase[k] = lane + 64 * k < S ? (u32)(lane + 64 * k) * (u32)S : 0u;
-    }
-    int mr[NR], loaded[NR];
-    i64 rv[NR], rl[NR];
-    u64 vfl[NR];
-#pragma unroll
-    for (int k = 0; k < NR; ++k) {
-        mr[k] = -1;
-        loaded[k] = -1;
-        rv[k] = 0;
-        rl[k] = 0;
-        vfl[k] = 0;
-    }
-    u64 FREEC[NR];     // unmatched columns (wave-uniform)
-#pragma unroll
-    for (int w = 0; w < NR; ++w) {
-        const int n = S - 64 * w;
-        FREEC[w] = n >= 64 ? ~0ull : (n <= 0 ? 0ull : ((1ull << n) - 1));
-    }
-
-    // cm of column d (uniform) as uniform words
-    auto col_mask = [&](int d, u64 (&out)[NR]) {
-        const int dl = d & 63;
-#pragma unroll
-        for (int w = 0; w < NR; ++w) {
-            if constexpr (NR == 2) out[w] = (d >> 6) ? rdl64(cm[1][w], dl) : rdl64(cm[0][w], dl);
-            else out[w] = rdl64(cm[0][w], dl);
+    // Residuals never exceed L, so when L < 2^31 the whole stage loop runs on 32-bit words: the
+    // residual matrix is repacked in place (flag in bit 31) and every per-stage subtraction,
+    // comparison and select is one instruction instead of two.
+    const bool narrow = L < ((i64)1 << 31);
+    if (narrow) {
+        u32* R32 = reinterpret_cast<u32*>(k2_smem);
+        for (int e0 = 0; e0 < S * S; e0 += 64) {
+            const int e = e0 + lane;
+            u64 v = 0;
+            if (e < S * S) v = R[e];
+            __syncthreads();                    // chunk read before its (lower) words are rewritten
+            if (e < S * S) R32[e] = (u32)v | ((v & VFLAG) ? 0x80000000u : 0u);
         }
-    };
-    auto lowest = [&](const u64 (&m)[NR]) -> int {
-        if constexpr (NR == 2) return m[0] ? __builtin_ctzll(m[0]) : 64 + __builtin_ctzll(m[1]);
-        else return __builtin_ctzll(m[0]);
-    };
-    auto any = [&](const u64 (&m)[NR]) -> bool {
-        if constexpr (NR == 2) return (m[0] | m[1]) != 0;
-        else return m[0] != 0;
-    };
-
-    auto augment = [&](int r0) -> bool {
-        u64 F[NR], VIS[NR];
-#pragma unroll
-        for (int w = 0; w < NR; ++w) {
-            F[w] = (r0 >> 6) == w ? 1ull << (r0 & 63) : 0;
-            VIS[w] = 0;
+        __syncthreads();
+    }
+    auto run = [&](auto tag) {
+        typedef decltype(tag) V;                // word type of the residuals
+        typedef std::make_signed_t<V> SV;
+        constexpr V VF = (V)((V)1 << (sizeof(V) * 8 - 1));   // the cell holds virtual bytes
+        V* Rv = reinterpret_cast<V*>(k2_smem);
+        auto wave_min = [&](V v) -> V {
+            if constexpr (sizeof(V) == 4) return wave_min_u32(v);
+            else return wave_min_u64(v);
+        };
+        int lid[NR];
+        u32 rowbase[NR];
+    #pragma unroll
+        for (int k = 0; k < NR; ++k) {
+            lid[k] = lane + 64 * k;
+            rowbase[k] = lane + 64 * k < S ? (u32)(lane + 64 * k) * (u32)S : 0u;
         }
-        int nfree = 0;
-#pragma unroll
-        for (int w = 0; w < NR; ++w) nfree += __builtin_popcountll(FREEC[w]);
-        const bool few = nfree <= 2;
-        int level = 1, dstar = -1, a = -1;
-        for (;;) {
-            if (few) {
-                // few unmatched columns: test each against the frontier with scalar work
-                u64 fr[NR];
-#pragma unroll
-                for (int w = 0; w < NR; ++w) fr[w] = FREEC[w];
-                while (any(fr)) {
-                    const int f = lowest(fr);
-                    u64 cmf[NR];
-                    col_mask(f, cmf);
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) cmf[w] &= F[w];
-                    if (any(cmf)) {
-                        dstar = f;
+        int mr[NR], loaded[NR];
+        SV rv[NR], rl[NR];
+        V vfl[NR];
+    #pragma unroll
+        for (int k = 0; k < NR; ++k) {
+            mr[k] = -1;
+            loaded[k] = -1;
+            rv[k] = 0;
+            rl[k] = 0;
+            vfl[k] = 0;
+        }
+        u64 FREEC[NR];     // unmatched columns (wave-uniform)
+    #pragma unroll
+        for (int w = 0; w < NR; ++w) {
+            const int n = S - 64 * w;
+            FREEC[w] = n >= 64 ? ~0ull : (n <= 0 ? 0ull : ((1ull << n) - 1));
+        }
+
+        // cm of column d (uniform) as uniform words
+        auto col_mask = [&](int d, u64 (&out)[NR]) {
+            const int dl = d & 63;
+    #pragma unroll
+            for (int w = 0; w < NR; ++w) {
+                if constexpr (NR == 2) out[w] = (d >> 6) ? rdl64(cm[1][w], dl) : rdl64(cm[0][w], dl);
+                else out[w] = rdl64(cm[0][w], dl);
+            }
+        };
+        auto lowest = [&](const u64 (&m)[NR]) -> int {
+            if constexpr (NR == 2) return m[0] ? __builtin_ctzll(m[0]) : 64 + __builtin_ctzll(m[1]);
+            else return __builtin_ctzll(m[0]);
+        };
+        auto any = [&](const u64 (&m)[NR]) -> bool {
+            if constexpr (NR == 2) return (m[0] | m[1]) != 0;
+            else return m[0] != 0;
+        };
+
+        auto augment = [&](int r0) -> bool {
+            u64 F[NR], VIS[NR];
+    #pragma unroll
+            for (int w = 0; w < NR; ++w) {
+                F[w] = (r0 >> 6) == w ? 1ull << (r0 & 63) : 0;
+                VIS[w] = 0;
+            }
+            int nfree = 0;
+    #pragma unroll
+            for (int w = 0; w < NR; ++w) nfree += __builtin_popcountll(FREEC[w]);
+            const bool few = nfree <= 2;
+            int level = 1, dstar = -1, a = -1;
+            for (;;) {
+                if (few) {
+                    // few unmatched columns: test each against the frontier with scalar work
+                    u64 fr[NR];
+    #pragma unroll
+                    for (int w = 0; w < NR; ++w) fr[w] = FREEC[w];
+                    while (any(fr)) {
+                        const int f = lowest(fr);
+                        u64 cmf[NR];
+                        col_mask(f, cmf);
+    #pragma unroll
+                        for (int w = 0; w < NR; ++w) cmf[w] &= F[w];
+                        if (any(cmf)) {
+                            dstar = f;
+                            a = lowest(cmf);
+                            break;
+                        }
+    #pragma unroll
+                        for (int w = 0; w < NR; ++w)
+                            if ((f >> 6) == w) fr[w] &= ~(1ull << (f & 63));
+                    }
+                    if (dstar >= 0) break;
+                }
+                u64 N[NR];
+    #pragma unroll
+                for (int k = 0; k < NR; ++k) {
+                    u64 cand = 0;
+    #pragma unroll
+                    for (int w = 0; w < NR; ++w) cand |= cm[k][w] & F[w];
+                    N[k] = ballot(cand != 0) & ~VIS[k];
+                }
+                if (!few) {
+                    u64 fr[NR];
+    #pragma unroll
+                    for (int w = 0; w < NR; ++w) fr[w] = N[w] & FREEC[w];
+                    if (any(fr)) {
+                        dstar = lowest(fr);
+                        u64 cmf[NR];
+                        col_mask(dstar, cmf);
+    #pragma unroll
+                        for (int w = 0; w < NR; ++w) cmf[w] &= F[w];
                         a = lowest(cmf);
                         break;
                     }
-#pragma unroll
-                    for (int w = 0; w < NR; ++w)
-                        if ((f >> 6) == w) fr[w] &= ~(1ull << (f & 63));
                 }
-                if (dstar >= 0) break;
+                if (!any(N)) return false;
+    #pragma unroll
+                for (int w = 0; w < NR; ++w) VIS[w] |= N[w];
+                if (level >= 2 && lane == 0) {
+    #pragma unroll
+                    for (int w = 0; w < NR; ++w) Fh[level * 2 + w] = F[w];
+                }
+    #pragma unroll
+                for (int k = 0; k < NR; ++k) {
+                    const int m = mr[k];
+                    u64 word;
+                    if constexpr (NR == 2) word = m < 64 ? N[0] : N[1];
+                    else word = N[0];
+                    F[k] = ballot(m >= 0 && ((word >> (m & 63)) & 1));
+                }
+                ++level;
             }
-            u64 N[NR];
-#pragma unroll
+            // flip the path: column dstar <- row a <- its old column <- ... <- r0
+            int d = dstar;
+            for (int hops = 0;; ++hops) {
+                if (hops > S) return false;
+                int prev;
+                if constexpr (NR == 2) prev = (a >> 6) ? (int)rdl(mr[1], a & 63) : (int)rdl(mr[0], a & 63);
+                else prev = (int)rdl(mr[0], a & 63);
+    #pragma unroll
+                for (int k = 0; k < NR; ++k) {
+                    mr[k] = (lane + 64 * k == a) ? d : mr[k];
+                }
+                if (a == r0) break;
+                d = prev;
+                --level;
+                u64 Fl[NR];
+                if (level == 1) {
+    #pragma unroll
+                    for (int w = 0; w < NR; ++w) Fl[w] = (r0 >> 6) == w ? 1ull << (r0 & 63) : 0;
+                } else {
+    #pragma unroll
+                    for (int w = 0; w < NR; ++w) {
+                        const u64 x = Fh[level * 2 + w];
+                        Fl[w] = ((u64)(u32)__builtin_amdgcn_readfirstlane((u32)(x >> 32)) << 32) |
+                                (u64)(u32)__builtin_amdgcn_readfirstlane((u32)x);
+                    }
+                }
+                u64 cmd[NR];
+                col_mask(d, cmd);
+    #pragma unroll
+                for (int w = 0; w < NR; ++w) cmd[w] &= Fl[w];
+                a = lowest(cmd);
+            }
+    #pragma unroll
+            for (int w = 0; w < NR; ++w)
+                if ((dstar >> 6) == w) FREEC[w] &= ~(1ull << (dstar & 63));
+            return true;
+        };
+
+        // Make rv / rl describe the cell each row is matched to now.  Loads are
+        // issued for every row (cheap, no exec juggling) and kept only where the
+        // match changed; the old cell's residual is written back where it is non-zero.
+        auto sync_matched = [&]() {
+            V x[NR];
+            bool ch[NR];
+    #pragma unroll
+            for (int k = 0; k < NR; ++k) {
+                ch[k] = mr[k] != loaded[k];
+                if (ch[k] && rv[k] > 0) Rv[rowbase[k] + (u32)loaded[k]] = (V)rv[k] | vfl[k];
+                x[k] = Rv[rowbase[k] + (u32)max(mr[k], 0)];
+            }
+            u64 anyv = 0;
+    #pragma unroll
+            for (int k = 0; k < NR; ++k) {
+                const V val = x[k] & (V)~VF;
+                const V fl = x[k] & VF;
+                rv[k] = ch[k] ? (SV)val : rv[k];
+                rl[k] = ch[k] ? (SV)val : rl[k];
+                anyv |= ballot(ch[k] && fl != 0);
+                vfl[k] = ch[k] ? fl : vfl[k];
+                loaded[k] = mr[k];
+            }
+            if (__builtin_expect(anyv != 0, 0)) {
+    #pragma unroll
+                for (int k = 0; k < NR; ++k) {
+                    if (ch[k] && vfl[k] != 0) {
+                        const int d = mr[k];
+                        const i64 l = max(PR[k], PC[d]);
+                        const i64 h = min(ER[k], EC[d]);
+                        const i64 av = (h > l ? h - l : 0) + (d == lid[k] ? diag[k] : 0);
+                        rl[k] = (i64)rv[k] > av ? (SV)((i64)rv[k] - av) : (SV)0;
+                    }
+                }
+            }
+        };
+
+        int status = 0;
+        for (int r0 = 0; r0 < S; ++r0)
+            if (!augment(r0)) { status = -3; break; }
+        if (status < 0) {
+            if (lane == 0) out_num[b] = status;
+            return;
+        }
+        sync_matched();
+    #pragma unroll
+        for (int k = 0; k < NR; ++k)
+            if (lane + 64 * k >= S) rv[k] = std::numeric_limits<SV>::max();     // never the minimum, never zero
+
+        int32_t* stg = out_stages + (size_t)b * max_stages * S;
+        i64* byt = out_bytes + (size_t)b * max_stages * S;
+        i64* cw = wsC + (size_t)b * max_stages;
+        i64 Lrem = L;
+        int s = 0;
+        int32_t* srow = stg;
+        i64* brow = byt;
+        // mr of a uniform row
+        auto mr_of = [&](int a) -> int {
+            if constexpr (NR == 2) {
+                const int x0 = (int)rdl((u32)mr[0], a & 63), x1 = (int)rdl((u32)mr[1], a & 63);
+                return (a & 64) ? x1 : x0;
+            } else {
+                return (int)rdl((u32)mr[0], a);
+            }
+        };
+        auto set_mr = [&](int a, int d) {
+    #pragma unroll
+            for (int k = 0; k < NR; ++k) mr[k] = lid[k] == a ? d : mr[k];
+        };
+        // columns (as a uniform mask per column slot) adjacent to any row of F
+        auto expand = [&](const u64 (&F)[NR], u64 (&N)[NR]) {
+    #pragma unroll
             for (int k = 0; k < NR; ++k) {
                 u64 cand = 0;
-#pragma unroll
+    #pragma unroll
                 for (int w = 0; w < NR; ++w) cand |= cm[k][w] & F[w];
-                N[k] = ballot(cand != 0) & ~VIS[k];
+                N[k] = ballot(cand != 0);
             }
-            if (!few) {
-                u64 fr[NR];
-#pragma unroll
-                for (int w = 0; w < NR; ++w) fr[w] = N[w] & FREEC[w];
-                if (any(fr)) {
-                    dstar = lowest(fr);
-                    u64 cmf[NR];
-                    col_mask(dstar, cmf);
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) cmf[w] &= F[w];
-                    a = lowest(cmf);
-                    break;
-                }
-            }
-            if (!any(N)) return false;
-#pragma unroll
-            for (int w = 0; w < NR; ++w) VIS[w] |= N[w];
-            if (level >= 2 && lane == 0) {
-#pragma unroll
-                for (int w = 0; w < NR; ++w) Fh[level * 2 + w] = F[w];
-            }
-#pragma unroll
+        };
+        // rows (uniform mask per row slot) whose matched column is in N
+        auto rows_matched_into = [&](const u64 (&N)[NR], u64 (&F)[NR]) {
+    #pragma unroll
             for (int k = 0; k < NR; ++k) {
                 const int m = mr[k];
                 u64 word;
@@ -354,278 +508,153 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 else word = N[0];
                 F[k] = ballot(m >= 0 && ((word >> (m & 63)) & 1));
             }
-            ++level;
-        }
-        // flip the path: column dstar <- row a <- its old column <- ... <- r0
-        int d = dstar;
-        for (int hops = 0;; ++hops) {
-            if (hops > S) return false;
-            int prev;
-            if constexpr (NR == 2) prev = (a >> 6) ? (int)rdl(mr[1], a & 63) : (int)rdl(mr[0], a & 63);
-            else prev = (int)rdl(mr[0], a & 63);
-#pragma unroll
+        };
+
+        for (;;) {
+            if (__builtin_expect(s >= max_stages, 0)) { status = -2; break; }
+            V mine = (V)rv[0];
+            if constexpr (NR == 2) mine = (V)rv[1] < mine ? (V)rv[1] : mine;
+            const i64 c64 = (i64)wave_min(mine);    // stage weight: wave-uniform, fits SV
+        const SV c = (SV)c64;
+            u64 Z[NR];
+            bool zero[NR];
+    #pragma unroll
             for (int k = 0; k < NR; ++k) {
-                mr[k] = (lane + 64 * k == a) ? d : mr[k];
-            }
-            if (a == r0) break;
-            d = prev;
-            --level;
-            u64 Fl[NR];
-            if (level == 1) {
-#pragma unroll
-                for (int w = 0; w < NR; ++w) Fl[w] = (r0 >> 6) == w ? 1ull << (r0 & 63) : 0;
-            } else {
-#pragma unroll
-                for (int w = 0; w < NR; ++w) {
-                    const u64 x = Fh[level * 2 + w];
-                    Fl[w] = ((u64)(u32)__builtin_amdgcn_readfirstlane((u32)(x >> 32)) << 32) |
-                            (u64)(u32)__builtin_amdgcn_readfirstlane((u32)x);
+                const SV real = c < rl[k] ? c : rl[k];
+                rl[k] -= real;
+                rv[k] -= c;
+                if (FULL || lid[k] < S) {
+                    srow[lid[k]] = real > 0 ? mr[k] : -1;
+                    brow[lid[k]] = (i64)real;
                 }
+                zero[k] = rv[k] == 0;
+                Z[k] = ballot(zero[k]);
             }
-            u64 cmd[NR];
-            col_mask(d, cmd);
-#pragma unroll
-            for (int w = 0; w < NR; ++w) cmd[w] &= Fl[w];
-            a = lowest(cmd);
-        }
-#pragma unroll
-        for (int w = 0; w < NR; ++w)
-            if ((dstar >> 6) == w) FREEC[w] &= ~(1ull << (dstar & 63));
-        return true;
-    };
+            cw[s] = c64;      // every lane stores the same word: no divergent branch on the path
+            ++s;
+            srow += S;
+            brow += S;
+            Lrem -= c64;
+            if (__builtin_expect(Lrem == 0, 0)) break;
 
-    // Make rv / rl describe the cell each row is matched to now.  Loads are
-    // issued for every row (cheap, no exec juggling) and kept only where the
-    // match changed; the old cell's residual is written back where it is non-zero.
-    auto sync_matched = [&]() {
-        u64 x[NR];
-        bool ch[NR];
-#pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            ch[k] = mr[k] != loaded[k];
-            if (ch[k] && rv[k] > 0) R[rowbase[k] + (u32)loaded[k]] = (u64)rv[k] | vfl[k];
-            x[k] = R[rowbase[k] + (u32)max(mr[k], 0)];
-        }
-        u64 anyv = 0;
-#pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            const u64 val = x[k] & ~VFLAG;
-            const u64 fl = x[k] & VFLAG;
-            rv[k] = ch[k] ? (i64)val : rv[k];
-            rl[k] = ch[k] ? (i64)val : rl[k];
-            anyv |= ballot(ch[k] && fl != 0);
-            vfl[k] = ch[k] ? fl : vfl[k];
-            loaded[k] = mr[k];
-        }
-        if (anyv) {
-#pragma unroll
-            for (int k = 0; k < NR; ++k) {
-                if (ch[k] && vfl[k] != 0) {
-                    const int d = mr[k];
-                    const i64 l = max(PR[k], PC[d]);
-                    const i64 h = min(ER[k], EC[d]);
-                    const i64 av = (h > l ? h - l : 0) + (d == lid[k] ? diag[k] : 0);
-                    rl[k] = rv[k] > av ? rv[k] - av : 0;
+            int nz = 0;
+    #pragma unroll
+            for (int w = 0; w < NR; ++w) nz += __builtin_popcountll(Z[w]);
+            bool done = false;
+            if (__builtin_expect(nz == 1, 1)) {
+                // ---- fast path: one exhausted cell (r0, f); f is the only unmatched column.
+                // Row r0 keeps naming f as its column until the flip; f is not adjacent to
+                // r0 any more, so r0 cannot enter a frontier through it.
+                const int r0 = lowest(Z);
+                const int f = mr_of(r0);
+                const u64 bit0 = 1ull << (r0 & 63);
+                u64 cmf[NR], N1[NR], F2[NR];
+                // KF = column slot of f, WR = mask word of r0 (compile-time in each branch)
+                auto level1 = [&](auto KFc, auto WRc) {
+                    constexpr int KF = decltype(KFc)::value, WR = decltype(WRc)::value;
+    #pragma unroll
+                    for (int w = 0; w < NR; ++w) cmf[w] = rdl64(cm[KF][w], f & 63);
+                    cmf[WR] &= ~bit0;
+                    wrlane64(cm[KF][WR], cmf[WR], f & 63);
+    #pragma unroll
+                    for (int k = 0; k < NR; ++k) N1[k] = ballot((cm[k][WR] & bit0) != 0);
+                };
+                if constexpr (NR == 2) {
+                    const int sel = ((f >> 6) << 1) | (r0 >> 6);
+                    if (sel == 0) level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+                    else if (sel == 1) level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
+                    else if (sel == 2) level1(std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
+                    else level1(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
+                } else {
+                    level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
                 }
-            }
-        }
-    };
-
-    int status = 0;
-    for (int r0 = 0; r0 < S; ++r0)
-        if (!augment(r0)) { status = -3; break; }
-    if (status < 0) {
-        if (lane == 0) out_num[b] = status;
-        return;
-    }
-    sync_matched();
-#pragma unroll
-    for (int k = 0; k < NR; ++k)
-        if (lane + 64 * k >= S) rv[k] = INT64_MAX;     // never the minimum, never zero
-
-    int32_t* stg = out_stages + (size_t)b * max_stages * S;
-    i64* byt = out_bytes + (size_t)b * max_stages * S;
-    i64* cw = wsC + (size_t)b * max_stages;
-    i64 Lrem = L;
-    int s = 0;
-    int32_t* srow = stg;
-    i64* brow = byt;
-    // mr of a uniform row
-    auto mr_of = [&](int a) -> int {
-        if constexpr (NR == 2) {
-            const int x0 = (int)rdl((u32)mr[0], a & 63), x1 = (int)rdl((u32)mr[1], a & 63);
-            return (a & 64) ? x1 : x0;
-        } else {
-            return (int)rdl((u32)mr[0], a);
-        }
-    };
-    auto set_mr = [&](int a, int d) {
-#pragma unroll
-        for (int k = 0; k < NR; ++k) mr[k] = lid[k] == a ? d : mr[k];
-    };
-    // columns (as a uniform mask per column slot) adjacent to any row of F
-    auto expand = [&](const u64 (&F)[NR], u64 (&N)[NR]) {
-#pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            u64 cand = 0;
-#pragma unroll
-            for (int w = 0; w < NR; ++w) cand |= cm[k][w] & F[w];
-            N[k] = ballot(cand != 0);
-        }
-    };
-    // rows (uniform mask per row slot) whose matched column is in N
-    auto rows_matched_into = [&](const u64 (&N)[NR], u64 (&F)[NR]) {
-#pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            const int m = mr[k];
-            u64 word;
-            if constexpr (NR == 2) word = m < 64 ? N[0] : N[1];
-            else word = N[0];
-            F[k] = ballot(m >= 0 && ((word >> (m & 63)) & 1));
-        }
-    };
-
-    for (;;) {
-        if (s >= max_stages) { status = -2; break; }
-        u64 mine = (u64)rv[0];
-        if constexpr (NR == 2) mine = (u64)rv[1] < mine ? (u64)rv[1] : mine;
-        const i64 c = (i64)wave_min_u64(mine);
-        u64 Z[NR];
-        bool zero[NR];
-#pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            const i64 real = c < rl[k] ? c : rl[k];
-            rl[k] -= real;
-            rv[k] -= c;
-            if (FULL || lid[k] < S) {
-                srow[lid[k]] = real > 0 ? mr[k] : -1;
-                brow[lid[k]] = real;
-            }
-            zero[k] = rv[k] == 0;
-            Z[k] = ballot(zero[k]);
-        }
-        if (lane == 0) cw[s] = c;
-        ++s;
-        srow += S;
-        brow += S;
-        Lrem -= c;
-        if (Lrem == 0) break;
-
-        int nz = 0;
-#pragma unroll
-        for (int w = 0; w < NR; ++w) nz += __builtin_popcountll(Z[w]);
-        bool done = false;
-        if (nz == 1) {
-            // ---- fast path: one exhausted cell (r0, f); f is the only unmatched column.
-            // Row r0 keeps naming f as its column until the flip; f is not adjacent to
-            // r0 any more, so r0 cannot enter a frontier through it.
-            const int r0 = lowest(Z);
-            const int f = mr_of(r0);
-            const u64 bit0 = 1ull << (r0 & 63);
-            u64 cmf[NR], N1[NR], F2[NR];
-            // KF = column slot of f, WR = mask word of r0 (compile-time in each branch)
-            auto level1 = [&](auto KFc, auto WRc) {
-                constexpr int KF = decltype(KFc)::value, WR = decltype(WRc)::value;
-#pragma unroll
-                for (int w = 0; w < NR; ++w) cmf[w] = rdl64(cm[KF][w], f & 63);
-                cmf[WR] &= ~bit0;
-                wrlane64(cm[KF][WR], cmf[WR], f & 63);
-#pragma unroll
-                for (int k = 0; k < NR; ++k) N1[k] = ballot((cm[k][WR] & bit0) != 0);
-            };
-            if constexpr (NR == 2) {
-                const int sel = ((f >> 6) << 1) | (r0 >> 6);
-                if (sel == 0) level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-                else if (sel == 1) level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
-                else if (sel == 2) level1(std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
-                else level1(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
-            } else {
-                level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-            }
-            // every row is matched here (r0 nominally), so no "unmatched" test is needed
-#pragma unroll
-            for (int k = 0; k < NR; ++k) {
-                const int m = mr[k];
-                u64 t;
-                if constexpr (NR == 2) t = (m & 64) ? (N1[1] >> (m & 63)) : (N1[0] >> (m & 63));
-                else t = N1[0] >> (m & 63);
-                F2[k] = ballot((t & 1) != 0);
-            }
-            u64 c2[NR];
-#pragma unroll
-            for (int w = 0; w < NR; ++w) c2[w] = cmf[w] & F2[w];
-            if (any(c2)) {
-                const int a1 = lowest(c2);
-                const int d1 = mr_of(a1);
-                set_mr(a1, f);
-                set_mr(r0, d1);
-                done = true;
-            } else if (any(N1)) {
-                set_mr(r0, -1);
-                u64 N2[NR], F3[NR], c3[NR];
-                expand(F2, N2);
-#pragma unroll
-                for (int w = 0; w < NR; ++w) N2[w] &= ~N1[w];
-                rows_matched_into(N2, F3);
-#pragma unroll
-                for (int w = 0; w < NR; ++w) c3[w] = cmf[w] & F3[w];
-                if (any(c3)) {
-                    const int a2 = lowest(c3);
-                    const int d2 = mr_of(a2);
-                    u64 cd[NR];
-                    col_mask(d2, cd);
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) cd[w] &= F2[w];
-                    const int a1 = lowest(cd);
+                // every row is matched here (r0 nominally), so no "unmatched" test is needed
+    #pragma unroll
+                for (int k = 0; k < NR; ++k) {
+                    const int m = mr[k];
+                    u64 t;
+                    if constexpr (NR == 2) t = (m & 64) ? (N1[1] >> (m & 63)) : (N1[0] >> (m & 63));
+                    else t = N1[0] >> (m & 63);
+                    F2[k] = ballot((t & 1) != 0);
+                }
+                u64 c2[NR];
+    #pragma unroll
+                for (int w = 0; w < NR; ++w) c2[w] = cmf[w] & F2[w];
+                if (__builtin_expect(any(c2), 1)) {
+                    const int a1 = lowest(c2);
                     const int d1 = mr_of(a1);
-                    set_mr(a2, f);
-                    set_mr(a1, d2);
+                    set_mr(a1, f);
                     set_mr(r0, d1);
                     done = true;
-                }
-            }
-            if (!done) {
-                // deeper than three levels: let the general search redo it
-                set_mr(r0, -1);
-#pragma unroll
-                for (int w = 0; w < NR; ++w)
-                    if ((f >> 6) == w) FREEC[w] |= 1ull << (f & 63);
-                if (!augment(r0)) { status = -3; break; }
-            }
-        } else {
-            // ---- general path: unmatch every exhausted cell first, then re-augment in order
-            u64 z[NR];
-#pragma unroll
-            for (int w = 0; w < NR; ++w) z[w] = Z[w];
-            while (any(z)) {
-                const int a = lowest(z);
-                const int d = mr_of(a);
-                const u64 bit = 1ull << (a & 63);
-                const bool here = lane == (d & 63);
-#pragma unroll
-                for (int k = 0; k < NR; ++k) {
-                    if ((d >> 6) == k) {
-#pragma unroll
-                        for (int w = 0; w < NR; ++w)
-                            if ((a >> 6) == w) cm[k][w] = here ? cm[k][w] & ~bit : cm[k][w];
-                        FREEC[k] |= 1ull << (d & 63);
+                } else if (any(N1)) {
+                    set_mr(r0, -1);
+                    u64 N2[NR], F3[NR], c3[NR];
+                    expand(F2, N2);
+    #pragma unroll
+                    for (int w = 0; w < NR; ++w) N2[w] &= ~N1[w];
+                    rows_matched_into(N2, F3);
+    #pragma unroll
+                    for (int w = 0; w < NR; ++w) c3[w] = cmf[w] & F3[w];
+                    if (any(c3)) {
+                        const int a2 = lowest(c3);
+                        const int d2 = mr_of(a2);
+                        u64 cd[NR];
+                        col_mask(d2, cd);
+    #pragma unroll
+                        for (int w = 0; w < NR; ++w) cd[w] &= F2[w];
+                        const int a1 = lowest(cd);
+                        const int d1 = mr_of(a1);
+                        set_mr(a2, f);
+                        set_mr(a1, d2);
+                        set_mr(r0, d1);
+                        done = true;
                     }
                 }
-#pragma unroll
+                if (__builtin_expect(!done, 0)) {
+                    // deeper than three levels: let the general search redo it
+                    set_mr(r0, -1);
+    #pragma unroll
+                    for (int w = 0; w < NR; ++w)
+                        if ((f >> 6) == w) FREEC[w] |= 1ull << (f & 63);
+                    if (!augment(r0)) { status = -3; break; }
+                }
+            } else {
+                // ---- general path: unmatch every exhausted cell first, then re-augment in order
+                u64 z[NR];
+    #pragma unroll
+                for (int w = 0; w < NR; ++w) z[w] = Z[w];
+                while (any(z)) {
+                    const int a = lowest(z);
+                    const int d = mr_of(a);
+                    const u64 bit = 1ull << (a & 63);
+                    const bool here = lane == (d & 63);
+    #pragma unroll
+                    for (int k = 0; k < NR; ++k) {
+                        if ((d >> 6) == k) {
+    #pragma unroll
+                            for (int w = 0; w < NR; ++w)
+                                if ((a >> 6) == w) cm[k][w] = here ? cm[k][w] & ~bit : cm[k][w];
+                            FREEC[k] |= 1ull << (d & 63);
+                        }
+                    }
+    #pragma unroll
+                    for (int w = 0; w < NR; ++w)
+                        if ((a >> 6) == w) z[w] &= ~bit;
+                }
+    #pragma unroll
+                for (int k = 0; k < NR; ++k) mr[k] = zero[k] ? -1 : mr[k];
+                bool ok = true;
+    #pragma unroll
                 for (int w = 0; w < NR; ++w)
-                    if ((a >> 6) == w) z[w] &= ~bit;
+                    for (u64 zz = Z[w]; zz && ok; zz &= zz - 1) ok = augment(64 * w + __builtin_ctzll(zz));
+                if (!ok) { status = -3; break; }
             }
-#pragma unroll
-            for (int k = 0; k < NR; ++k) mr[k] = zero[k] ? -1 : mr[k];
-            bool ok = true;
-#pragma unroll
-            for (int w = 0; w < NR; ++w)
-                for (u64 zz = Z[w]; zz && ok; zz &= zz - 1) ok = augment(64 * w + __builtin_ctzll(zz));
-            if (!ok) { status = -3; break; }
+            sync_matched();
         }
-        sync_matched();
-    }
-    if (lane == 0) out_num[b] = status < 0 ? status : s;
+        if (lane == 0) out_num[b] = status < 0 ? status : s;
+    };
+    if (narrow) run((u32)0);
+    else run((u64)0);
 }
 
 }  // namespace fastk

@@ -191,6 +191,39 @@ def test_degenerate_inputs(oracle, torch_cuda):
     compare_batch(oracle, S, G, 400e9, 50e9, tr, res)
 
 
+def test_residual_width_boundary(oracle, torch_cuda):
+    """The decomposition runs on 32-bit residuals when the largest row/column sum of the
+    per-lane server matrix is below 2^31 and on 64-bit ones otherwise: matrices on both sides
+    of that boundary, alone and mixed in one batch."""
+    S, G = 5, 2
+    N = S * G
+    rng = np.random.default_rng(31)
+    mats = []
+    for L in [(1 << 31) - 2, (1 << 31) - 1, 1 << 31, (1 << 31) + 1, (1 << 32) + 5]:
+        t = rng.integers(0, 50, size=(N, N)).astype(np.int64)
+        t4 = t.reshape(S, G, S, G)
+        t4[1, :, 3, :] = 0
+        t4[1, 0, 3, 1] = G * L - int(t4[1].sum(axis=(0, 2))[[0, 2, 4]].sum())  # row 1 of Q sums to about L
+        mats.append(t)
+        say(f"[parity] width boundary L ~ {L}")
+    tr = np.stack(mats)
+    res = run_gpu(torch_cuda, S, G, 400e9, 50e9, tr)
+    compare_batch(oracle, S, G, 400e9, 50e9, tr, res)
+    for b in range(len(mats)):
+        one = run_gpu(torch_cuda, S, G, 400e9, 50e9, tr[b:b + 1])
+        K = int(res["K"][b])
+        assert int(one["K"][0]) == K
+        assert np.array_equal(one["stages"][0, :K], res["stages"][b, :K])
+        assert np.array_equal(one["bytes"][0, :K], res["bytes"][b, :K])
+    # the exact boundary: a single pair with Q = 2^31 - 1 and Q = 2^31
+    for q in [(1 << 31) - 1, 1 << 31]:
+        t = np.zeros((1, N, N), np.int64)
+        t[0, 0, N - 1] = G * q
+        r = run_gpu(torch_cuda, S, G, 400e9, 50e9, t)
+        compare_batch(oracle, S, G, 400e9, 50e9, t, r)
+        assert int(r["K"][0]) == 1 and int(r["bytes"][0, 0].max()) == q
+
+
 def test_negative_entry_status_is_per_matrix(oracle, torch_cuda):
     S, G = 4, 8
     rng = np.random.default_rng(5)
