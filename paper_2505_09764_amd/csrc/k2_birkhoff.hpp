@@ -422,14 +422,26 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         // Make rv / rl describe the cell each row is matched to now.  Loads are
         // issued for every row (cheap, no exec juggling) and kept only where the
         // match changed; the old cell's residual is written back where it is non-zero.
-        auto sync_matched = [&]() {
+        // FIRST: the call after the initial matching, when nothing has been loaded yet.  Later
+        // calls of the FULL variant (every lane slot a real, matched row) write the old cell back
+        // unconditionally - for an unchanged row that rewrites what LDS already holds, for an
+        // exhausted cell it stores the zero that is its true residual - which saves the
+        // predicates and the exec juggling on the dependent path.
+        auto sync_matched = [&](auto first_tag) {
+            constexpr bool FIRST = decltype(first_tag)::value;
+            constexpr bool PLAIN = FULL && !FIRST;
             V x[NR];
             bool ch[NR];
     #pragma unroll
             for (int k = 0; k < NR; ++k) {
                 ch[k] = mr[k] != loaded[k];
-                if (ch[k] && rv[k] > 0) Rv[rowbase[k] + (u32)loaded[k]] = (V)rv[k] | vfl[k];
-                x[k] = Rv[rowbase[k] + (u32)max(mr[k], 0)];
+                if constexpr (PLAIN) {
+                    Rv[rowbase[k] + (u32)loaded[k]] = (V)rv[k] | vfl[k];
+                    x[k] = Rv[rowbase[k] + (u32)mr[k]];
+                } else {
+                    if (ch[k] && rv[k] > 0) Rv[rowbase[k] + (u32)loaded[k]] = (V)rv[k] | vfl[k];
+                    x[k] = Rv[rowbase[k] + (u32)max(mr[k], 0)];
+                }
             }
             u64 anyv = 0;
     #pragma unroll
@@ -438,7 +450,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 const V fl = x[k] & VF;
                 rv[k] = ch[k] ? (SV)val : rv[k];
                 rl[k] = ch[k] ? (SV)val : rl[k];
-                anyv |= ballot(ch[k] && fl != 0);
+                anyv |= ballot(ch[k]) & ballot(fl != 0);
                 vfl[k] = ch[k] ? fl : vfl[k];
                 loaded[k] = mr[k];
             }
@@ -463,7 +475,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             if (lane == 0) out_num[b] = status;
             return;
         }
-        sync_matched();
+        sync_matched(std::true_type{});
     #pragma unroll
         for (int k = 0; k < NR; ++k)
             if (lane + 64 * k >= S) rv[k] = std::numeric_limits<SV>::max();     // never the minimum, never zero
@@ -540,7 +552,6 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             int nz = 0;
     #pragma unroll
             for (int w = 0; w < NR; ++w) nz += __builtin_popcountll(Z[w]);
-            bool done = false;
             if (__builtin_expect(nz == 1, 1)) {
                 // ---- fast path: one exhausted cell (r0, f); f is the only unmatched column.
                 // Row r0 keeps naming f as its column until the flip; f is not adjacent to
@@ -585,8 +596,9 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     const int d1 = mr_of(a1);
                     set_mr(a1, f);
                     set_mr(r0, d1);
-                    done = true;
-                } else if (any(N1)) {
+                } else {
+                    bool done = false;
+                    if (any(N1)) {
                     set_mr(r0, -1);
                     u64 N2[NR], F3[NR], c3[NR];
                     expand(F2, N2);
@@ -609,14 +621,15 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                         set_mr(r0, d1);
                         done = true;
                     }
-                }
-                if (__builtin_expect(!done, 0)) {
-                    // deeper than three levels: let the general search redo it
-                    set_mr(r0, -1);
+                    }
+                    if (!done) {
+                        // deeper than three levels: let the general search redo it
+                        set_mr(r0, -1);
     #pragma unroll
-                    for (int w = 0; w < NR; ++w)
-                        if ((f >> 6) == w) FREEC[w] |= 1ull << (f & 63);
-                    if (!augment(r0)) { status = -3; break; }
+                        for (int w = 0; w < NR; ++w)
+                            if ((f >> 6) == w) FREEC[w] |= 1ull << (f & 63);
+                        if (!augment(r0)) status = -3;     // leaves the loop before the sync
+                    }
                 }
             } else {
                 // ---- general path: unmatch every exhausted cell first, then re-augment in order
@@ -647,9 +660,10 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     #pragma unroll
                 for (int w = 0; w < NR; ++w)
                     for (u64 zz = Z[w]; zz && ok; zz &= zz - 1) ok = augment(64 * w + __builtin_ctzll(zz));
-                if (!ok) { status = -3; break; }
+                if (!ok) status = -3;
             }
-            sync_matched();
+            if (__builtin_expect(status < 0, 0)) break;     // a row is unmatched: nothing to sync
+            sync_matched(std::false_type{});
         }
         if (lane == 0) out_num[b] = status < 0 ? status : s;
     };
