@@ -560,24 +560,31 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 const int f = mr_of(r0);
                 const u64 bit0 = 1ull << (r0 & 63);
                 u64 cmf[NR], N1[NR], F2[NR];
-                // KF = column slot of f, WR = mask word of r0 (compile-time in each branch)
-                auto level1 = [&](auto KFc, auto WRc) {
-                    constexpr int KF = decltype(KFc)::value, WR = decltype(WRc)::value;
+                // KF = column slot of f (compile-time in each branch); the mask word of r0 is handled
+                // by data: clr[w] is bit r0 in its own word and 0 in the other
+                u64 clr[NR];
     #pragma unroll
-                    for (int w = 0; w < NR; ++w) cmf[w] = rdl64(cm[KF][w], f & 63);
-                    cmf[WR] &= ~bit0;
-                    wrlane64(cm[KF][WR], cmf[WR], f & 63);
+                for (int w = 0; w < NR; ++w) clr[w] = (r0 >> 6) == w ? bit0 : 0ull;
+                auto level1 = [&](auto KFc) {
+                    constexpr int KF = decltype(KFc)::value;
     #pragma unroll
-                    for (int k = 0; k < NR; ++k) N1[k] = ballot((cm[k][WR] & bit0) != 0);
+                    for (int w = 0; w < NR; ++w) {
+                        cmf[w] = rdl64(cm[KF][w], f & 63) & ~clr[w];
+                        wrlane64(cm[KF][w], cmf[w], f & 63);
+                    }
+    #pragma unroll
+                    for (int k = 0; k < NR; ++k) {
+                        u64 t = 0;
+    #pragma unroll
+                        for (int w = 0; w < NR; ++w) t |= cm[k][w] & clr[w];
+                        N1[k] = ballot(t != 0);
+                    }
                 };
                 if constexpr (NR == 2) {
-                    const int sel = ((f >> 6) << 1) | (r0 >> 6);
-                    if (sel == 0) level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-                    else if (sel == 1) level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
-                    else if (sel == 2) level1(std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
-                    else level1(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
+                    if ((f >> 6) == 0) level1(std::integral_constant<int, 0>{});
+                    else level1(std::integral_constant<int, 1>{});
                 } else {
-                    level1(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+                    level1(std::integral_constant<int, 0>{});
                 }
                 // every row is matched here (r0 nominally), so no "unmatched" test is needed
     #pragma unroll
