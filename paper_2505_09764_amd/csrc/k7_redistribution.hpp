@@ -148,9 +148,31 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
             ln[u] = by[(size_t)ss[u] * S + ac];
         }
     };
+    // A batch: first all fetch-and-adds (they queue up in the LDS pipe in program order, one
+    // wait for the lot), then all stores.
     auto process = [&](const int (&ss)[U], const int (&dd)[U], const i64 (&ln)[U]) {
+        i64 off[U];
+        int pos[U];
+        bool sends[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) stage(ss[u], dd[u], ln[u]);
+        for (int u = 0; u < U; ++u) {
+            sends[u] = dd[u] >= 0 && dd[u] < S;
+            const int w = (sends[u] ? dd[u] : 0) * RD_ROWS + lane;
+            off[u] = (i64)atomicAdd(reinterpret_cast<u64*>(&sent[w]), (u64)(sends[u] ? ln[u] : 0));
+            if constexpr (LISTS) pos[u] = atomicAdd(&next[w], sends[u] ? 1 : 0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const i64 o = sends[u] ? off[u] : 0;
+            if constexpr (LISTS) {
+                if (live && sends[u] && pos[u] < max_stages) {   // always below for a permutation
+                    list_s[lbase + pos[u]] = ss[u];
+                    list_off[lbase + pos[u]] = o;
+                    list_len[lbase + pos[u]] = ln[u];
+                }
+            }
+            if (live) off_out[(size_t)ss[u] * S + a] = o;
+        }
     };
     // Three batch buffers take the roles "being processed", "rows in flight", "indices in
     // flight" in turn, so no register is copied while its load is outstanding.
