@@ -44,9 +44,8 @@ struct fast_plan {
     int rd_cap_B;
     int32_t* rdStart;      // [B][S][S] start of the pair's list within its source server's row
     int32_t* rdCnt;        // [B][S][S] stages in which the pair occurs
-    int32_t* rdListS;      // [B][S][max_stages] stage index
-    i64* rdListOff;        // [B][S][max_stages] send offset
-    i64* rdListLen;        // [B][S][max_stages] bytes per lane
+    fastk::i64x2* rdList;  // [B][S][max_stages] (bytes per lane, stage) per (stage, source) that sends,
+                           //                    grouped by destination, in execution order
     int last_B;            // B of the most recent synthesis call (0 = none)
     // timing: four events per recorded call
     int timing;
@@ -195,8 +194,8 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     p->soKeys = nullptr;
     p->soIdx = nullptr;
     p->rd_cap_B = 0;
-    p->rdStart = p->rdCnt = p->rdListS = nullptr;
-    p->rdListOff = p->rdListLen = nullptr;
+    p->rdStart = p->rdCnt = nullptr;
+    p->rdList = nullptr;
     p->last_B = 0;
     p->timing = 0;
     p->n_timed = 0;
@@ -399,7 +398,7 @@ int fast_stage_offsets_batched(fast_plan_t* p, int B, const int32_t* stages,
     hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S, false),
                        stream, stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
                        stage_order, reinterpret_cast<i64*>(out_stage_offset), nullptr, nullptr,
-                       nullptr, nullptr, nullptr, p->S, p->max_stages);
+                       nullptr, p->S, p->max_stages);
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     return FAST_OK;
 }
@@ -417,21 +416,18 @@ int fast_redistribution_batched(fast_plan_t* p, int B, const int64_t* traffic,
     if (B > 65535) return FAST_ERR_UNSUPPORTED;
     const size_t S = p->S, M = p->max_stages;
     if (B > p->rd_cap_B) {
-        if (p->rdListOff) (void)hipFree(p->rdListOff);
-        p->rdListOff = nullptr;
+        if (p->rdList) (void)hipFree(p->rdList);
+        p->rdList = nullptr;
         p->rd_cap_B = 0;
         const size_t nPair = (size_t)B * S * S, nList = (size_t)B * S * M;
         unsigned char* base = nullptr;
-        if (hipMalloc(&base, nList * (2 * sizeof(i64) + sizeof(int32_t)) +
-                                 2 * nPair * sizeof(int32_t)) != hipSuccess) {
+        if (hipMalloc(&base, nList * sizeof(fastk::i64x2) + 2 * nPair * sizeof(int32_t)) !=
+            hipSuccess) {
             (void)hipGetLastError();
             return FAST_ERR_OOM;
         }
-        // 8-byte arrays first so that every array is naturally aligned
-        p->rdListOff = reinterpret_cast<i64*>(base);
-        p->rdListLen = p->rdListOff + nList;
-        p->rdListS = reinterpret_cast<int32_t*>(p->rdListLen + nList);
-        p->rdStart = p->rdListS + nList;
+        p->rdList = reinterpret_cast<fastk::i64x2*>(base);     // 16-byte entries first: aligned
+        p->rdStart = reinterpret_cast<int32_t*>(p->rdList + nList);
         p->rdCnt = p->rdStart + nPair;
         p->rd_cap_B = B;
     }
@@ -445,11 +441,11 @@ int fast_redistribution_batched(fast_plan_t* p, int B, const int64_t* traffic,
     hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S, true),
                        stream, stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
                        stage_order, reinterpret_cast<i64*>(out_stage_offset), p->rdStart, p->rdCnt,
-                       p->rdListS, p->rdListOff, p->rdListLen, p->S, p->max_stages);
+                       p->rdList, p->S, p->max_stages);
     hipLaunchKernelGGL(fastk::rd_volumes, dim3(p->S * p->S, B), dim3(64), 0, stream,
                        reinterpret_cast<const i64*>(traffic), reinterpret_cast<const i64*>(rebalance),
-                       num_stages, p->rdStart, p->rdCnt, p->rdListS, p->rdListOff, p->rdListLen,
-                       redis, p->S, p->G, p->max_stages);
+                       num_stages, p->rdStart, p->rdCnt, p->rdList, redis, p->S, p->G,
+                       p->max_stages);
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     return FAST_OK;
 }
@@ -521,7 +517,7 @@ void fast_plan_destroy(fast_plan_t* p) {
     free_workspace(p);
     free_spo_workspace(p);
     if (p->soKeys) (void)hipFree(p->soKeys);
-    if (p->rdListOff) (void)hipFree(p->rdListOff);
+    if (p->rdList) (void)hipFree(p->rdList);
     if (p->ev) {
         for (int c = 0; c < FAST_MAX_TIMED_CALLS; ++c)
             for (int k = 0; k < 4; ++k)

@@ -64,8 +64,7 @@ __global__ void __launch_bounds__(RD_ROWS)
 rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_bytes,
            const int32_t* __restrict__ num_stages, const int32_t* __restrict__ order,
            i64* __restrict__ out_offset, int32_t* __restrict__ lstart, int32_t* __restrict__ lcnt,
-           int32_t* __restrict__ list_s, i64* __restrict__ list_off, i64* __restrict__ list_len,
-           int S, int max_stages) {
+           i64x2* __restrict__ list, int S, int max_stages) {
     extern __shared__ __align__(16) unsigned char rd_smem[];
     constexpr int U = RD_UNROLL;
     const int b = blockIdx.y;
@@ -116,16 +115,15 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
     auto stage = [&](int s, int d, i64 len) {
         const bool sends = d >= 0 && d < S;
         const int w = (sends ? d : 0) * RD_ROWS + lane;
-        // fetch-and-add in one LDS instruction: the adds of a batch queue up in the LDS pipe
-        // in program order instead of each waiting for the previous read to come back
         const i64 before = (i64)atomicAdd(reinterpret_cast<u64*>(&sent[w]), (u64)(sends ? len : 0));
         const i64 off = sends ? before : 0;
         if constexpr (LISTS) {
             const int pos = atomicAdd(&next[w], sends ? 1 : 0);
             if (live && sends && pos < max_stages) {    // pos < max_stages for any permutation
-                list_s[lbase + pos] = s;
-                list_off[lbase + pos] = off;
-                list_len[lbase + pos] = len;
+                i64x2 entry;
+                entry.x = len;
+                entry.y = s;
+                list[lbase + pos] = entry;
             }
         }
         if (live) off_out[(size_t)s * S + a] = off;
@@ -166,9 +164,10 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
             const i64 o = sends[u] ? off[u] : 0;
             if constexpr (LISTS) {
                 if (live && sends[u] && pos[u] < max_stages) {   // always below for a permutation
-                    list_s[lbase + pos[u]] = ss[u];
-                    list_off[lbase + pos[u]] = o;
-                    list_len[lbase + pos[u]] = ln[u];
+                    i64x2 entry;                 // one 16-byte store: (bytes per lane, stage)
+                    entry.x = ln[u];
+                    entry.y = ss[u];
+                    list[lbase + pos[u]] = entry;
                 }
             }
             if (live) off_out[(size_t)ss[u] * S + a] = o;
@@ -300,19 +299,22 @@ __device__ __forceinline__ I rd_volume(I m) {
     return v;
 }
 
+// The pair's list is in execution order, so a stage's send offset is the running sum of the
+// bytes of the entries before it.
 template <typename I>
 __device__ __forceinline__ void rd_run_pair(const i64 lo64[8], const i64 hi64[8], bool diag,
-                                            const int32_t* __restrict__ ls,
-                                            const i64* __restrict__ lo_, const i64* __restrict__ ll,
-                                            int n, u64* __restrict__ redis) {
+                                            const i64x2* __restrict__ list, int n,
+                                            u64* __restrict__ redis) {
     I lo[8], hi[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) { lo[i] = (I)lo64[i]; hi[i] = (I)hi64[i]; }
+    i64 off = 0;
     for (int e = 0; e < n; ++e) {
-        const int s = ls[e];
-        const i64 off = lo_[e];
-        const i64 end = off + ll[e];
+        const i64x2 entry = list[e];
+        const int s = (int)entry.y;
+        const i64 end = off + entry.x;
         I m = rd_cell<I>(lo, hi, (I)off, (I)end);
+        off = end;
         if (diag) m = 0;
         const I v = rd_volume<I>(m);
         if ((threadIdx.x & 63) == 0 && v > 0) atomicMax(&redis[s], (u64)v);
@@ -323,8 +325,7 @@ __device__ __forceinline__ void rd_run_pair(const i64 lo64[8], const i64 hi64[8]
 __global__ void __launch_bounds__(64)
 rd_volumes(const i64* __restrict__ traffic, const i64* __restrict__ X,
            const int32_t* __restrict__ num_stages, const int32_t* __restrict__ lstart,
-           const int32_t* __restrict__ lcnt, const int32_t* __restrict__ list_s,
-           const i64* __restrict__ list_off, const i64* __restrict__ list_len,
+           const int32_t* __restrict__ lcnt, const i64x2* __restrict__ list,
            u64* __restrict__ redis, int S, int G, int max_stages) {
     __shared__ i64 t[RD_TILE_WORDS];
     const int b = blockIdx.y;
@@ -343,9 +344,9 @@ rd_volumes(const i64* __restrict__ traffic, const i64* __restrict__ X,
     const bool diag = (lane >> 3) == (lane & 7);
     u64* out = redis + (size_t)b * max_stages;
     if (total < ((i64)1 << 31))
-        rd_run_pair<int>(lo, hi, diag, list_s + lbase, list_off + lbase, list_len + lbase, n, out);
+        rd_run_pair<int>(lo, hi, diag, list + lbase, n, out);
     else
-        rd_run_pair<i64>(lo, hi, diag, list_s + lbase, list_off + lbase, list_len + lbase, n, out);
+        rd_run_pair<i64>(lo, hi, diag, list + lbase, n, out);
 }
 
 // grid (S, n_sel), 64 threads: one wavefront per (selected stage, source server).
