@@ -285,17 +285,60 @@ __device__ __forceinline__ int dpp_ror8(int v) {
 }
 __device__ __forceinline__ i64 dpp_ror8(i64 v) { return dpp_i64<0x128>(v); }
 
+// Exchange between the two 16-lane rows of each half (xor 16) and between the two halves
+// (xor 32) with the gfx950 row-swap instructions: swap(v, v) returns the pair
+// (rows 0,0,2,2 | rows 1,1,3,3) resp. (lower half twice | upper half twice), so one
+// commutative operation on the pair leaves the reduction in every lane - no LDS round trip.
+struct rd_sum { template <typename T> __device__ T operator()(T a, T b) const { return a + b; } };
+struct rd_max { template <typename T> __device__ T operator()(T a, T b) const { return a > b ? a : b; } };
+template <bool ROWS, typename OP>
+__device__ __forceinline__ int rd_swap_reduce(int v, OP op) {
+    if constexpr (ROWS) {
+        const auto r = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+        return op((int)r[0], (int)r[1]);
+    } else {
+        const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+        return op((int)r[0], (int)r[1]);
+    }
+}
+template <bool ROWS, typename OP>
+__device__ __forceinline__ i64 rd_swap_reduce(i64 v, OP op) {
+    const unsigned lo = (unsigned)(u64)v, hi = (unsigned)((u64)v >> 32);
+    i64 a, b;
+    if constexpr (ROWS) {
+        const auto l = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        const auto h = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        a = (i64)(((u64)h[0] << 32) | l[0]);
+        b = (i64)(((u64)h[1] << 32) | l[1]);
+    } else {
+        const auto l = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+        const auto h = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+        a = (i64)(((u64)h[0] << 32) | l[0]);
+        b = (i64)(((u64)h[1] << 32) | l[1]);
+    }
+    return op(a, b);
+}
+template <int CTRL> __device__ __forceinline__ int rd_dpp_get(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL> __device__ __forceinline__ i64 rd_dpp_get(i64 v) { return dpp_i64<CTRL>(v); }
+
 // Largest, over the 8 GPUs, of max(bytes forwarded, bytes received): m is the lane's
-// cell (k, j) of the redistribution matrix with the diagonal already zeroed.
+// cell (k, j) of the redistribution matrix with the diagonal already zeroed.  The result is
+// in every lane.
 template <typename I>
 __device__ __forceinline__ I rd_volume(I m) {
-    const I fwd = dpp_sum8(m);                    // row k: what lane k forwards
-    I recv = m + dpp_ror8(m);                     // column j: rows k and k ^ 1 ...
-    recv += __shfl_xor(recv, 16, 64);             // ... the other half of the 32 ...
-    recv += __shfl_xor(recv, 32, 64);             // ... and the other 32 lanes
+    const I fwd = dpp_sum8(m);                              // row k: what lane k forwards
+    I recv = m + dpp_ror8(m);                               // column j: rows k and k ^ 1 ...
+    recv = rd_swap_reduce<true>(recv, rd_sum());            // ... the other 16-lane row ...
+    recv = rd_swap_reduce<false>(recv, rd_sum());           // ... and the other half
     I v = max(fwd, recv);
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+    v = max(v, rd_dpp_get<0xB1>(v));                        // quad_perm [1,0,3,2]
+    v = max(v, rd_dpp_get<0x4E>(v));                        // quad_perm [2,3,0,1]
+    v = max(v, rd_dpp_get<0x141>(v));                       // row_half_mirror
+    v = max(v, rd_dpp_get<0x140>(v));                       // row_mirror
+    v = rd_swap_reduce<true>(v, rd_max());
+    v = rd_swap_reduce<false>(v, rd_max());
     return v;
 }
 
