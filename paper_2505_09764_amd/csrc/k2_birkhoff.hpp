@@ -266,7 +266,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         };
         int lid[NR];
         u32 rowbase[NR];
-    #pragma unroll
+#pragma unroll
         for (int k = 0; k < NR; ++k) {
             lid[k] = lane + 64 * k;
             rowbase[k] = lane + 64 * k < S ? (u32)(lane + 64 * k) * (u32)S : 0u;
@@ -274,7 +274,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         int mr[NR], loaded[NR];
         SV rv[NR], rl[NR];
         V vfl[NR];
-    #pragma unroll
+#pragma unroll
         for (int k = 0; k < NR; ++k) {
             mr[k] = -1;
             loaded[k] = -1;
@@ -283,7 +283,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             vfl[k] = 0;
         }
         u64 FREEC[NR];     // unmatched columns (wave-uniform)
-    #pragma unroll
+#pragma unroll
         for (int w = 0; w < NR; ++w) {
             const int n = S - 64 * w;
             FREEC[w] = n >= 64 ? ~0ull : (n <= 0 ? 0ull : ((1ull << n) - 1));
@@ -292,7 +292,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         // cm of column d (uniform) as uniform words
         auto col_mask = [&](int d, u64 (&out)[NR]) {
             const int dl = d & 63;
-    #pragma unroll
+#pragma unroll
             for (int w = 0; w < NR; ++w) {
                 if constexpr (NR == 2) out[w] = (d >> 6) ? rdl64(cm[1][w], dl) : rdl64(cm[0][w], dl);
                 else out[w] = rdl64(cm[0][w], dl);
@@ -309,13 +309,13 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 
         auto augment = [&](int r0) -> bool {
             u64 F[NR], VIS[NR];
-    #pragma unroll
+#pragma unroll
             for (int w = 0; w < NR; ++w) {
                 F[w] = (r0 >> 6) == w ? 1ull << (r0 & 63) : 0;
                 VIS[w] = 0;
             }
             int nfree = 0;
-    #pragma unroll
+#pragma unroll
             for (int w = 0; w < NR; ++w) nfree += __builtin_popcountll(FREEC[w]);
             const bool few = nfree <= 2;
             int level = 1, dstar = -1, a = -1;
@@ -323,55 +323,55 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 if (few) {
                     // few unmatched columns: test each against the frontier with scalar work
                     u64 fr[NR];
-    #pragma unroll
+#pragma unroll
                     for (int w = 0; w < NR; ++w) fr[w] = FREEC[w];
                     while (any(fr)) {
                         const int f = lowest(fr);
                         u64 cmf[NR];
                         col_mask(f, cmf);
-    #pragma unroll
+#pragma unroll
                         for (int w = 0; w < NR; ++w) cmf[w] &= F[w];
                         if (any(cmf)) {
                             dstar = f;
                             a = lowest(cmf);
                             break;
                         }
-    #pragma unroll
+#pragma unroll
                         for (int w = 0; w < NR; ++w)
                             if ((f >> 6) == w) fr[w] &= ~(1ull << (f & 63));
                     }
                     if (dstar >= 0) break;
                 }
                 u64 N[NR];
-    #pragma unroll
+#pragma unroll
                 for (int k = 0; k < NR; ++k) {
                     u64 cand = 0;
-    #pragma unroll
+#pragma unroll
                     for (int w = 0; w < NR; ++w) cand |= cm[k][w] & F[w];
                     N[k] = ballot(cand != 0) & ~VIS[k];
                 }
                 if (!few) {
                     u64 fr[NR];
-    #pragma unroll
+#pragma unroll
                     for (int w = 0; w < NR; ++w) fr[w] = N[w] & FREEC[w];
                     if (any(fr)) {
                         dstar = lowest(fr);
                         u64 cmf[NR];
                         col_mask(dstar, cmf);
-    #pragma unroll
+#pragma unroll
                         for (int w = 0; w < NR; ++w) cmf[w] &= F[w];
                         a = lowest(cmf);
                         break;
                     }
                 }
                 if (!any(N)) return false;
-    #pragma unroll
+#pragma unroll
                 for (int w = 0; w < NR; ++w) VIS[w] |= N[w];
                 if (level >= 2 && lane == 0) {
-    #pragma unroll
+#pragma unroll
                     for (int w = 0; w < NR; ++w) Fh[level * 2 + w] = F[w];
                 }
-    #pragma unroll
+#pragma unroll
                 for (int k = 0; k < NR; ++k) {
                     const int m = mr[k];
                     u64 word;
@@ -388,7 +388,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 int prev;
                 if constexpr (NR == 2) prev = (a >> 6) ? (int)rdl(mr[1], a & 63) : (int)rdl(mr[0], a & 63);
                 else prev = (int)rdl(mr[0], a & 63);
-    #pragma unroll
+#pragma unroll
                 for (int k = 0; k < NR; ++k) {
                     mr[k] = (lane + 64 * k == a) ? d : mr[k];
                 }
@@ -397,10 +397,10 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 --level;
                 u64 Fl[NR];
                 if (level == 1) {
-    #pragma unroll
+#pragma unroll
                     for (int w = 0; w < NR; ++w) Fl[w] = (r0 >> 6) == w ? 1ull << (r0 & 63) : 0;
                 } else {
-    #pragma unroll
+#pragma unroll
                     for (int w = 0; w < NR; ++w) {
                         const u64 x = Fh[level * 2 + w];
                         Fl[w] = ((u64)(u32)__builtin_amdgcn_readfirstlane((u32)(x >> 32)) << 32) |
@@ -409,11 +409,11 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 }
                 u64 cmd[NR];
                 col_mask(d, cmd);
-    #pragma unroll
+#pragma unroll
                 for (int w = 0; w < NR; ++w) cmd[w] &= Fl[w];
                 a = lowest(cmd);
             }
-    #pragma unroll
+#pragma unroll
             for (int w = 0; w < NR; ++w)
                 if ((dstar >> 6) == w) FREEC[w] &= ~(1ull << (dstar & 63));
             return true;
@@ -432,7 +432,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             constexpr bool PLAIN = FULL && !FIRST;
             V x[NR];
             bool ch[NR];
-    #pragma unroll
+#pragma unroll
             for (int k = 0; k < NR; ++k) {
                 ch[k] = mr[k] != loaded[k];
                 if constexpr (PLAIN) {
@@ -444,7 +444,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 }
             }
             u64 anyv = 0;
-    #pragma unroll
+#pragma unroll
             for (int k = 0; k < NR; ++k) {
                 const V val = x[k] & (V)~VF;
                 const V fl = x[k] & VF;
@@ -455,7 +455,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 loaded[k] = mr[k];
             }
             if (__builtin_expect(anyv != 0, 0)) {
-    #pragma unroll
+#pragma unroll
                 for (int k = 0; k < NR; ++k) {
                     if (ch[k] && vfl[k] != 0) {
                         const int d = mr[k];
@@ -476,7 +476,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             return;
         }
         sync_matched(std::true_type{});
-    #pragma unroll
+#pragma unroll
         for (int k = 0; k < NR; ++k)
             if (lane + 64 * k >= S) rv[k] = std::numeric_limits<SV>::max();     // never the minimum, never zero
 
@@ -497,22 +497,22 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             }
         };
         auto set_mr = [&](int a, int d) {
-    #pragma unroll
+#pragma unroll
             for (int k = 0; k < NR; ++k) mr[k] = lid[k] == a ? d : mr[k];
         };
         // columns (as a uniform mask per column slot) adjacent to any row of F
         auto expand = [&](const u64 (&F)[NR], u64 (&N)[NR]) {
-    #pragma unroll
+#pragma unroll
             for (int k = 0; k < NR; ++k) {
                 u64 cand = 0;
-    #pragma unroll
+#pragma unroll
                 for (int w = 0; w < NR; ++w) cand |= cm[k][w] & F[w];
                 N[k] = ballot(cand != 0);
             }
         };
         // rows (uniform mask per row slot) whose matched column is in N
         auto rows_matched_into = [&](const u64 (&N)[NR], u64 (&F)[NR]) {
-    #pragma unroll
+#pragma unroll
             for (int k = 0; k < NR; ++k) {
                 const int m = mr[k];
                 u64 word;
@@ -527,10 +527,10 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             V mine = (V)rv[0];
             if constexpr (NR == 2) mine = (V)rv[1] < mine ? (V)rv[1] : mine;
             const i64 c64 = (i64)wave_min(mine);    // stage weight: wave-uniform, fits SV
-        const SV c = (SV)c64;
+            const SV c = (SV)c64;
             u64 Z[NR];
             bool zero[NR];
-    #pragma unroll
+#pragma unroll
             for (int k = 0; k < NR; ++k) {
                 const SV real = c < rl[k] ? c : rl[k];
                 rl[k] -= real;
@@ -550,7 +550,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             if (__builtin_expect(Lrem == 0, 0)) break;
 
             int nz = 0;
-    #pragma unroll
+#pragma unroll
             for (int w = 0; w < NR; ++w) nz += __builtin_popcountll(Z[w]);
             if (__builtin_expect(nz == 1, 1)) {
                 // ---- fast path: one exhausted cell (r0, f); f is the only unmatched column.
@@ -563,19 +563,19 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 // KF = column slot of f (compile-time in each branch); the mask word of r0 is handled
                 // by data: clr[w] is bit r0 in its own word and 0 in the other
                 u64 clr[NR];
-    #pragma unroll
+#pragma unroll
                 for (int w = 0; w < NR; ++w) clr[w] = (r0 >> 6) == w ? bit0 : 0ull;
                 auto level1 = [&](auto KFc) {
                     constexpr int KF = decltype(KFc)::value;
-    #pragma unroll
+#pragma unroll
                     for (int w = 0; w < NR; ++w) {
                         cmf[w] = rdl64(cm[KF][w], f & 63) & ~clr[w];
                         wrlane64(cm[KF][w], cmf[w], f & 63);
                     }
-    #pragma unroll
+#pragma unroll
                     for (int k = 0; k < NR; ++k) {
                         u64 t = 0;
-    #pragma unroll
+#pragma unroll
                         for (int w = 0; w < NR; ++w) t |= cm[k][w] & clr[w];
                         N1[k] = ballot(t != 0);
                     }
@@ -587,7 +587,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     level1(std::integral_constant<int, 0>{});
                 }
                 // every row is matched here (r0 nominally), so no "unmatched" test is needed
-    #pragma unroll
+#pragma unroll
                 for (int k = 0; k < NR; ++k) {
                     const int m = mr[k];
                     u64 t;
@@ -596,7 +596,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     F2[k] = ballot((t & 1) != 0);
                 }
                 u64 c2[NR];
-    #pragma unroll
+#pragma unroll
                 for (int w = 0; w < NR; ++w) c2[w] = cmf[w] & F2[w];
                 if (__builtin_expect(any(c2), 1)) {
                     const int a1 = lowest(c2);
@@ -606,33 +606,33 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 } else {
                     bool done = false;
                     if (any(N1)) {
-                    set_mr(r0, -1);
-                    u64 N2[NR], F3[NR], c3[NR];
-                    expand(F2, N2);
-    #pragma unroll
-                    for (int w = 0; w < NR; ++w) N2[w] &= ~N1[w];
-                    rows_matched_into(N2, F3);
-    #pragma unroll
-                    for (int w = 0; w < NR; ++w) c3[w] = cmf[w] & F3[w];
-                    if (any(c3)) {
-                        const int a2 = lowest(c3);
-                        const int d2 = mr_of(a2);
-                        u64 cd[NR];
-                        col_mask(d2, cd);
-    #pragma unroll
-                        for (int w = 0; w < NR; ++w) cd[w] &= F2[w];
-                        const int a1 = lowest(cd);
-                        const int d1 = mr_of(a1);
-                        set_mr(a2, f);
-                        set_mr(a1, d2);
-                        set_mr(r0, d1);
-                        done = true;
-                    }
+                        set_mr(r0, -1);
+                        u64 N2[NR], F3[NR], c3[NR];
+                        expand(F2, N2);
+#pragma unroll
+                        for (int w = 0; w < NR; ++w) N2[w] &= ~N1[w];
+                        rows_matched_into(N2, F3);
+#pragma unroll
+                        for (int w = 0; w < NR; ++w) c3[w] = cmf[w] & F3[w];
+                        if (any(c3)) {
+                            const int a2 = lowest(c3);
+                            const int d2 = mr_of(a2);
+                            u64 cd[NR];
+                            col_mask(d2, cd);
+#pragma unroll
+                            for (int w = 0; w < NR; ++w) cd[w] &= F2[w];
+                            const int a1 = lowest(cd);
+                            const int d1 = mr_of(a1);
+                            set_mr(a2, f);
+                            set_mr(a1, d2);
+                            set_mr(r0, d1);
+                            done = true;
+                        }
                     }
                     if (!done) {
                         // deeper than three levels: let the general search redo it
                         set_mr(r0, -1);
-    #pragma unroll
+#pragma unroll
                         for (int w = 0; w < NR; ++w)
                             if ((f >> 6) == w) FREEC[w] |= 1ull << (f & 63);
                         if (!augment(r0)) status = -3;     // leaves the loop before the sync
@@ -641,30 +641,30 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             } else {
                 // ---- general path: unmatch every exhausted cell first, then re-augment in order
                 u64 z[NR];
-    #pragma unroll
+#pragma unroll
                 for (int w = 0; w < NR; ++w) z[w] = Z[w];
                 while (any(z)) {
                     const int a = lowest(z);
                     const int d = mr_of(a);
                     const u64 bit = 1ull << (a & 63);
                     const bool here = lane == (d & 63);
-    #pragma unroll
+#pragma unroll
                     for (int k = 0; k < NR; ++k) {
                         if ((d >> 6) == k) {
-    #pragma unroll
+#pragma unroll
                             for (int w = 0; w < NR; ++w)
                                 if ((a >> 6) == w) cm[k][w] = here ? cm[k][w] & ~bit : cm[k][w];
                             FREEC[k] |= 1ull << (d & 63);
                         }
                     }
-    #pragma unroll
+#pragma unroll
                     for (int w = 0; w < NR; ++w)
                         if ((a >> 6) == w) z[w] &= ~bit;
                 }
-    #pragma unroll
+#pragma unroll
                 for (int k = 0; k < NR; ++k) mr[k] = zero[k] ? -1 : mr[k];
                 bool ok = true;
-    #pragma unroll
+#pragma unroll
                 for (int w = 0; w < NR; ++w)
                     for (u64 zz = Z[w]; zz && ok; zz &= zz - 1) ok = augment(64 * w + __builtin_ctzll(zz));
                 if (!ok) status = -3;
