@@ -27,8 +27,16 @@
 //     matrix to a valid form") is never stored: pouring row deficits into column
 //     deficits in ascending order makes A[a][d] the overlap of two prefix-sum
 //     intervals (plus the diagonal term); cells that hold virtual bytes are
-//     flagged in bit 63 of their LDS word and the overlap is recomputed only
-//     when such a cell gets matched.
+//     flagged in the top bit of their LDS word and the overlap is recomputed only
+//     when such a cell gets matched;
+//   * no residual exceeds L, the largest row/column sum, so when L < 2^31 the matrix
+//     is repacked in place to 32-bit words and the stage loop runs on 32-bit
+//     registers; when S fills the lane slots exactly (64 or 128) the stage loop
+//     carries no bounds predicates.  Predicated LDS writes and mid-loop exits cost a
+//     lone wavefront far more than their instruction count suggests (exec-mask
+//     save/restore pairs, scalar branches at 11-13 cycles per instruction), so the
+//     dependent path avoids them: unconditional write-back of the old matched cell,
+//     the stage weight stored by every lane, error exits checked once per stage.
 //
 // Canonical choices that make the result a function of the matrix alone (the
 // paper leaves them open): level-synchronous search from one unmatched row, the
