@@ -44,7 +44,7 @@ struct fast_plan {
     int rd_cap_B;
     int32_t* rdStart;      // [B][S][S] start of the pair's list within its source server's row
     int32_t* rdCnt;        // [B][S][S] stages in which the pair occurs
-    fastk::i64x2* rdList;  // [B][S][max_stages] (bytes per lane, stage) per (stage, source) that sends,
+    fastk::i64x2* rdList;  // [B][S][max_stages + 1] (bytes per lane, stage) per (stage, source) that sends,
                            //                    grouped by destination, in execution order
     int last_B;            // B of the most recent synthesis call (0 = none)
     // timing: four events per recorded call
@@ -152,6 +152,20 @@ k2_fn k2_kernel(int S) {
     return &fastk::k2_birkhoff<1, false>;
 }
 
+// The stage-walk kernel: with or without pair lists, with or without a stage order, and the
+// variant without store predicates when S is a multiple of its 64 source servers per wavefront.
+typedef void (*rd_offsets_fn)(const int32_t*, const i64*, const int32_t*, const int32_t*, i64*, int32_t*,
+                              int32_t*, fastk::i64x2*, int, int);
+rd_offsets_fn rd_offsets_kernel(int S, bool lists, bool ordered) {
+    const bool all = S % fastk::RD_ROWS == 0;
+    if (lists) {
+        if (ordered) return all ? &fastk::rd_offsets<true, true, true> : &fastk::rd_offsets<true, true, false>;
+        return all ? &fastk::rd_offsets<true, false, true> : &fastk::rd_offsets<true, false, false>;
+    }
+    if (ordered) return all ? &fastk::rd_offsets<false, true, true> : &fastk::rd_offsets<false, true, false>;
+    return all ? &fastk::rd_offsets<false, false, true> : &fastk::rd_offsets<false, false, false>;
+}
+
 int next_pow2(int v) {
     int n = 1;
     while (n < v) n <<= 1;
@@ -213,12 +227,9 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)(next_pow2(p->max_stages) * sizeof(i64)));
     if (e == hipSuccess && fastk::rd_offsets_lds_bytes(S, true) > 48 * 1024) {
-        const void* kern[4] = {reinterpret_cast<const void*>(&fastk::rd_offsets<true, true>),
-                               reinterpret_cast<const void*>(&fastk::rd_offsets<true, false>),
-                               reinterpret_cast<const void*>(&fastk::rd_offsets<false, true>),
-                               reinterpret_cast<const void*>(&fastk::rd_offsets<false, false>)};
         for (int k = 0; k < 4 && e == hipSuccess; ++k)
-            e = hipFuncSetAttribute(kern[k], hipFuncAttributeMaxDynamicSharedMemorySize,
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(rd_offsets_kernel(S, k < 2, k % 2 == 0)),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)fastk::rd_offsets_lds_bytes(S, k < 2));
     }
     if (e != hipSuccess) {
@@ -394,7 +405,7 @@ int fast_stage_offsets_batched(fast_plan_t* p, int B, const int32_t* stages,
     if (!stages || !stage_bytes || !num_stages || !out_stage_offset) return FAST_ERR_INVALID_ARG;
     if (B > 65535) return FAST_ERR_UNSUPPORTED;
     const dim3 grid((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS, B);
-    auto kern = stage_order ? &fastk::rd_offsets<false, true> : &fastk::rd_offsets<false, false>;
+    auto kern = rd_offsets_kernel(p->S, false, stage_order != nullptr);
     hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S, false),
                        stream, stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
                        stage_order, reinterpret_cast<i64*>(out_stage_offset), nullptr, nullptr,
@@ -419,7 +430,7 @@ int fast_redistribution_batched(fast_plan_t* p, int B, const int64_t* traffic,
         if (p->rdList) (void)hipFree(p->rdList);
         p->rdList = nullptr;
         p->rd_cap_B = 0;
-        const size_t nPair = (size_t)B * S * S, nList = (size_t)B * S * M;
+        const size_t nPair = (size_t)B * S * S, nList = (size_t)B * S * (M + 1);
         unsigned char* base = nullptr;
         if (hipMalloc(&base, nList * sizeof(fastk::i64x2) + 2 * nPair * sizeof(int32_t)) !=
             hipSuccess) {
@@ -437,7 +448,7 @@ int fast_redistribution_batched(fast_plan_t* p, int B, const int64_t* traffic,
                                                                               : 2048)),
                        dim3(256), 0, stream, redis, nR);
     const dim3 grid((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS, B);
-    auto kern = stage_order ? &fastk::rd_offsets<true, true> : &fastk::rd_offsets<true, false>;
+    auto kern = rd_offsets_kernel(p->S, true, stage_order != nullptr);
     hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S, true),
                        stream, stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
                        stage_order, reinterpret_cast<i64*>(out_stage_offset), p->rdStart, p->rdCnt,

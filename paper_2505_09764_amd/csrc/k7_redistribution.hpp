@@ -59,7 +59,10 @@ __global__ void __launch_bounds__(256) rd_zero(u64* __restrict__ p, size_t n) {
 // row -> the running offset in LDS), so it is software-pipelined by hand: while batch n
 // of RD_UNROLL stages is processed, the rows of batch n+1 and the indices of batch n+2
 // are in flight.
-template <bool LISTS, bool ORDERED>
+// ALL: S is a multiple of RD_ROWS, every lane owns a real source server (no store predicate).
+// The pair lists have max_stages + 1 slots per source server: slot max_stages is a dump for the
+// lanes that do not send in a stage, so that the list store needs no predicate either.
+template <bool LISTS, bool ORDERED, bool ALL>
 __global__ void __launch_bounds__(RD_ROWS)
 rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_bytes,
            const int32_t* __restrict__ num_stages, const int32_t* __restrict__ order,
@@ -74,7 +77,7 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
     if (K <= 0) return;
     i64* sent = reinterpret_cast<i64*>(rd_smem);                    // [d][lane]
     int32_t* next = reinterpret_cast<int32_t*>(sent + (size_t)RD_ROWS * S);   // [d][lane]
-    const bool live = a < S;
+    const bool live = ALL || a < S;
     const int ac = live ? a : S - 1;                                // clamped: loads stay in range
     for (int d = 0; d < S; ++d) {
         sent[d * RD_ROWS + lane] = 0;
@@ -108,7 +111,7 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
         }
     }
 
-    const size_t lbase = ((size_t)b * S + ac) * max_stages;
+    const size_t lbase = ((size_t)b * S + ac) * (size_t)(max_stages + 1);
     // one stage: running offset of the pair (a, d) in LDS, optional list entry, send offset out.
     // Branch-free for an idle row (d < 0): it adds 0 to word 0 of the lane's column.  Lanes
     // beyond S work on a copy of row S-1 in their own LDS column and store nothing.
@@ -163,12 +166,12 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
         for (int u = 0; u < U; ++u) {
             const i64 o = sends[u] ? off[u] : 0;
             if constexpr (LISTS) {
-                if (live && sends[u] && pos[u] < max_stages) {   // always below for a permutation
-                    i64x2 entry;                 // one 16-byte store: (bytes per lane, stage)
-                    entry.x = ln[u];
-                    entry.y = ss[u];
-                    list[lbase + pos[u]] = entry;
-                }
+                i64x2 entry;                     // one 16-byte store: (bytes per lane, stage)
+                entry.x = ln[u];
+                entry.y = ss[u];
+                // pos < max_stages for any permutation; everything else goes to the dump slot
+                const int slot = sends[u] && pos[u] < max_stages ? pos[u] : max_stages;
+                if (live) list[lbase + slot] = entry;
             }
             if (live) off_out[(size_t)ss[u] * S + a] = o;
         }
@@ -382,7 +385,7 @@ rd_volumes(const i64* __restrict__ traffic, const i64* __restrict__ X,
     const size_t tile = ((size_t)b * N + (size_t)a * G) * N + (size_t)d * G;
     i64 lo[8], hi[8];
     const i64 total = rd_intervals(traffic + tile, X + tile, (size_t)N, G, t, lo, hi);
-    const size_t lbase = ((size_t)b * S + a) * max_stages + lstart[pair];
+    const size_t lbase = ((size_t)b * S + a) * (size_t)(max_stages + 1) + lstart[pair];
     const int lane = threadIdx.x & 63;
     const bool diag = (lane >> 3) == (lane & 7);
     u64* out = redis + (size_t)b * max_stages;
