@@ -58,6 +58,18 @@ def test_argument_checks_without_device(fastlib):
     assert fastlib.fast_plan_set_timing(None, 1) == b.FAST_ERR_INVALID_ARG
     assert fastlib.fast_plan_timed_calls(None) == -1
     assert fastlib.fast_plan_kernel_ms(None, 0, None) == b.FAST_ERR_INVALID_ARG
+    # every other entry point rejects a missing plan before anything else
+    E = b.FAST_ERR_INVALID_ARG
+    assert fastlib.fast_plan_set_wakeup_delay(None, 0.0) == E
+    assert fastlib.fast_spreadout_batched(None, 1, None, None, None) == E
+    assert fastlib.fast_stage_order_batched(None, 1, None, None, None, None) == E
+    assert fastlib.fast_build_traffic_batched(None, 1, 1, None, None, 1, None, None, None) == E
+    assert fastlib.fast_stage_offsets_batched(None, 1, None, None, None, None, None, None) == E
+    assert fastlib.fast_redistribution_batched(None, 1, None, None, None, None, None, None, None,
+                                               None, None) == E
+    assert fastlib.fast_redistribution_matrices(None, 1, None, None, None, None, None, None, 1, None,
+                                                None, None) == E
+    assert fastlib.fast_pipeline_time_batched(None, 1, None, None, None, None, None) == E
     fastlib.fast_plan_destroy(None)        # no-op
 
 

@@ -431,3 +431,48 @@ def test_stage_order(oracle, torch_cuda, ci, B):
         assert np.array_equal(o[b, :K], want), f"matrix {b}: order differs"
         assert (o[b, K:] == -1).all()
     syn.close()
+
+
+def test_error_codes_with_a_plan(torch_cuda):
+    """Host-detected errors (include/fast.h): negative return code, nothing enqueued."""
+    from paper_2505_09764_amd import binding as b
+    torch = torch_cuda
+    L = b.lib()
+    syn = b.Synthesizer(3, 2, 400e9, 50e9)
+    P = syn.plan
+    t = torch.ones((2, 6, 6), dtype=torch.int64, device="cuda:0")
+    out = syn.alloc_outputs(2)
+    ptr = lambda x: x.data_ptr()
+    args = [ptr(t), ptr(out.rebalance), ptr(out.stages), ptr(out.stage_bytes), ptr(out.num_stages),
+            ptr(out.predicted_time)]
+    assert L.fast_synthesize_batched(P, 0, *args, None) == b.FAST_OK            # B = 0: nothing to do
+    assert L.fast_synthesize_batched(P, 0, None, None, None, None, None, None, None) == b.FAST_OK
+    assert L.fast_synthesize_batched(P, -1, *args, None) == b.FAST_ERR_INVALID_ARG
+    assert L.fast_synthesize_batched(P, 65536, *args, None) == b.FAST_ERR_UNSUPPORTED
+    for k in range(6):                                                            # any NULL buffer
+        bad = list(args)
+        bad[k] = None
+        assert L.fast_synthesize_batched(P, 2, *bad, None) == b.FAST_ERR_INVALID_ARG
+    assert L.fast_plan_set_wakeup_delay(P, -1.0) == b.FAST_ERR_INVALID_ARG
+    assert L.fast_plan_set_wakeup_delay(P, float("nan")) == b.FAST_ERR_INVALID_ARG
+    sp = torch.empty((2, 2), dtype=torch.float64, device="cuda:0")
+    assert L.fast_spreadout_batched(P, 2, None, ptr(sp), None) == b.FAST_ERR_INVALID_ARG
+    assert L.fast_spreadout_batched(P, -3, ptr(t), ptr(sp), None) == b.FAST_ERR_INVALID_ARG
+    assert L.fast_build_traffic_batched(P, 2, 0, ptr(t), ptr(t), 1, ptr(t), ptr(t), None) == \
+        b.FAST_ERR_INVALID_ARG                                                    # E < 1
+    assert L.fast_build_traffic_batched(P, 2, 4, ptr(t), ptr(t), 0, ptr(t), ptr(t), None) == \
+        b.FAST_ERR_INVALID_ARG                                                    # token_bytes <= 0
+    assert L.fast_stage_order_batched(P, 2, None, ptr(out.num_stages), ptr(out.stages), None) == \
+        b.FAST_ERR_INVALID_ARG
+    assert L.fast_stage_offsets_batched(P, 2, ptr(out.stages), None, ptr(out.num_stages), None,
+                                        ptr(out.stage_bytes), None) == b.FAST_ERR_INVALID_ARG
+    assert L.fast_redistribution_matrices(P, 2, ptr(t), ptr(t), ptr(t), ptr(t), ptr(t), ptr(t), -1,
+                                          ptr(t), ptr(t), None) == b.FAST_ERR_INVALID_ARG
+    assert L.fast_redistribution_matrices(P, 2, ptr(t), ptr(t), ptr(t), ptr(t), ptr(t), ptr(t), 0,
+                                          None, None, None) == b.FAST_OK          # nothing selected
+    assert L.fast_plan_kernel_ms(P, 0, (b.ctypes.c_float * 3)()) == b.FAST_ERR_INVALID_ARG  # nothing timed
+    # the plan still works after all of that
+    syn.synthesize(t, out)
+    torch.cuda.synchronize()
+    assert (out.num_stages.cpu().numpy() >= 0).all()
+    syn.close()
