@@ -62,10 +62,13 @@ typedef unsigned int u32;
 constexpr int K2_THREADS = 64;
 constexpr u64 VFLAG = 1ull << 63;      // LDS word flag: the cell holds virtual bytes
 
-inline size_t k2_lds_bytes(int S) {
-    // R[S][S], column deficit intervals PC[S], EC[S], frontier history [(S+2)][2]
+// R[S][S], column deficit intervals PC[S], EC[S], frontier history [(S+2)][2]
+__host__ __device__ inline size_t k2_lds_data_bytes(int S) {
     return (size_t)S * S * 8 + (size_t)2 * S * 8 + (size_t)(S + 2) * 16;
 }
+// ... plus one spare word per lane slot and one in front: the lane slots that hold no row
+// (S below 64 * NR) read and write there, so the per-stage reload needs no bounds predicate
+inline size_t k2_lds_bytes(int S) { return k2_lds_data_bytes(S) + (size_t)(2 * 64 + 1) * 8; }
 
 __device__ __forceinline__ u64 ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 __device__ __forceinline__ u32 rdl(u32 v, int lane) { return (u32)__builtin_amdgcn_readlane(v, lane); }
@@ -277,7 +280,10 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 #pragma unroll
         for (int k = 0; k < NR; ++k) {
             lid[k] = lane + 64 * k;
-            rowbase[k] = lane + 64 * k < S ? (u32)(lane + 64 * k) * (u32)S : 0u;
+            // a slot without a row keeps mr = loaded = -1: base + (-1) is its spare word
+            // (the first reload, before any row is loaded, reads base + 0: the next spare word)
+            const u32 spare = (u32)(k2_lds_data_bytes(S) / sizeof(V)) + (u32)(lane + 64 * k) + 1u;
+            rowbase[k] = lane + 64 * k < S ? (u32)(lane + 64 * k) * (u32)S : spare;
         }
         int mr[NR], loaded[NR];
         SV rv[NR], rl[NR];
@@ -431,13 +437,13 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         // issued for every row (cheap, no exec juggling) and kept only where the
         // match changed; the old cell's residual is written back where it is non-zero.
         // FIRST: the call after the initial matching, when nothing has been loaded yet.  Later
-        // calls of the FULL variant (every lane slot a real, matched row) write the old cell back
-        // unconditionally - for an unchanged row that rewrites what LDS already holds, for an
-        // exhausted cell it stores the zero that is its true residual - which saves the
-        // predicates and the exec juggling on the dependent path.
+        // calls (every row matched; lane slots without a row work on their spare word) write the
+        // old cell back unconditionally - for an unchanged row that rewrites what LDS already
+        // holds, for an exhausted cell it stores the zero that is its true residual - which saves
+        // the predicates and the exec juggling on the dependent path.
         auto sync_matched = [&](auto first_tag) {
             constexpr bool FIRST = decltype(first_tag)::value;
-            constexpr bool PLAIN = FULL && !FIRST;
+            constexpr bool PLAIN = !FIRST;
             V x[NR];
             bool ch[NR];
 #pragma unroll
