@@ -215,7 +215,9 @@ struct Matcher {
     int S;
     const std::vector<i64>& R;
     std::vector<int> mr, mc;  // row -> matched column, column -> matched row
-    Matcher(int S_, const std::vector<i64>& R_) : S(S_), R(R_), mr(S_, -1), mc(S_, -1) {}
+    i64 thr;                  // a cell is an edge while it holds at least thr bytes (1: the support)
+    Matcher(int S_, const std::vector<i64>& R_, i64 thr_ = 1)
+        : S(S_), R(R_), mr(S_, -1), mc(S_, -1), thr(thr_) {}
 
     bool augment(int r0) {
         std::vector<char> visited(S, 0), inF(S, 0);
@@ -226,7 +228,7 @@ struct Matcher {
             for (int d = 0; d < S; ++d) {
                 if (visited[d]) continue;
                 for (int a = 0; a < S; ++a)
-                    if (inF[a] && R[(size_t)a * S + d] > 0) {
+                    if (inF[a] && R[(size_t)a * S + d] >= thr) {
                         parent[d] = a;  // lowest-numbered frontier row
                         fresh.push_back(d);
                         break;
@@ -255,6 +257,23 @@ struct Matcher {
     }
 };
 
+// One stage from a perfect matching mr (row -> column): the weight is the smallest
+// matched residual; every matched cell loses it, real bytes first.  Returns the weight.
+i64 take_stage(int S, const std::vector<int>& mr, std::vector<i64>& R, std::vector<i64>& Rreal,
+               int32_t* stage_row, i64* bytes_row) {
+    i64 c = R[(size_t)0 * S + mr[0]];
+    for (int a = 1; a < S; ++a) c = std::min(c, R[(size_t)a * S + mr[a]]);
+    for (int a = 0; a < S; ++a) {
+        const int d = mr[a];
+        const i64 real = std::min(c, Rreal[(size_t)a * S + d]);
+        Rreal[(size_t)a * S + d] -= real;
+        R[(size_t)a * S + d] -= c;
+        stage_row[a] = real > 0 ? d : -1;
+        bytes_row[a] = real;
+    }
+    return c;
+}
+
 int decompose(int S, const i64* Q, const i64* A, int cap, int32_t* stages, i64* bytes) {
     std::vector<i64> R((size_t)S * S), Rreal((size_t)S * S);
     std::vector<i64> rowsum(S, 0);
@@ -274,16 +293,7 @@ int decompose(int S, const i64* Q, const i64* A, int cap, int32_t* stages, i64* 
     int s = 0;
     for (;;) {
         if (s >= cap) return -2;
-        i64 c = R[(size_t)0 * S + M.mr[0]];
-        for (int a = 1; a < S; ++a) c = std::min(c, R[(size_t)a * S + M.mr[a]]);
-        for (int a = 0; a < S; ++a) {
-            const int d = M.mr[a];
-            const i64 real = std::min(c, Rreal[(size_t)a * S + d]);
-            Rreal[(size_t)a * S + d] -= real;
-            R[(size_t)a * S + d] -= c;
-            stages[(size_t)s * S + a] = real > 0 ? d : -1;
-            bytes[(size_t)s * S + a] = real;
-        }
+        const i64 c = take_stage(S, M.mr, R, Rreal, stages + (size_t)s * S, bytes + (size_t)s * S);
         Lrem -= c;
         ++s;
         if (Lrem == 0) return s;
@@ -294,6 +304,98 @@ int decompose(int S, const i64* Q, const i64* A, int cap, int32_t* stages, i64* 
         for (int a : freed)
             if (!M.augment(a)) return -3;
     }
+}
+
+// ---------------------------------------------------------------------------
+// Variant of step 5 with fewer, larger stages (Section 4.4 "Number of stages":
+// fewer stages are preferable since each costs a synchronisation, and the minimum
+// is NP-hard to find; the paper itself stops at "any valid decomposition").  The
+// greedy rule taken here, which is not the paper's: every stage removes as much
+// weight as one stage can, i.e. its matching is a bottleneck assignment of the
+// residual - a perfect matching whose smallest cell is as large as possible.
+//
+//  * bottleneck value t* of R = the largest t such that the cells with R >= t
+//    contain a perfect matching (equivalently the maximum over all perfect
+//    matchings of their smallest cell).  t* is one of the cell values, and a
+//    perfect matching that exists for t exists for every smaller t, so a binary
+//    search over the sorted distinct values is exact; existence is decided by a
+//    plain depth-first augmenting search (Kuhn), which shares nothing with the
+//    canonical Matcher;
+//  * the stage's matching = the canonical matching (rules at decompose()) of the
+//    graph {R >= t*}, built from nothing by augmenting rows 0..S-1 in order; its
+//    smallest cell is t* and that is the stage weight;
+//  * real bytes before virtual bytes, idle rows, outputs, return values: as in
+//    decompose().
+// The residual only shrinks, so the stage weights never increase; the stage-count
+// bound of Section 4.4 holds for any choice of matchings.  Which matchings come
+// out is this variant's own rule ("parity unpinned" by the paper); the bottleneck
+// value is pinned by brute force over all permutations and by a library matching.
+// ---------------------------------------------------------------------------
+bool kuhn_try(int S, const std::vector<i64>& R, i64 t, int a, std::vector<char>& seen,
+              std::vector<int>& owner) {
+    for (int d = 0; d < S; ++d) {
+        if (R[(size_t)a * S + d] < t || seen[d]) continue;
+        seen[d] = 1;
+        if (owner[d] < 0 || kuhn_try(S, R, t, owner[d], seen, owner)) {
+            owner[d] = a;
+            return true;
+        }
+    }
+    return false;
+}
+
+bool has_perfect_matching(int S, const std::vector<i64>& R, i64 t) {
+    std::vector<int> owner(S, -1);
+    for (int a = 0; a < S; ++a) {
+        std::vector<char> seen(S, 0);
+        if (!kuhn_try(S, R, t, a, seen, owner)) return false;
+    }
+    return true;
+}
+
+// 0 if even the support of R holds no perfect matching
+i64 bottleneck_value(int S, const std::vector<i64>& R) {
+    std::vector<i64> vals;
+    for (i64 v : R)
+        if (v > 0) vals.push_back(v);
+    std::sort(vals.begin(), vals.end());
+    vals.erase(std::unique(vals.begin(), vals.end()), vals.end());
+    i64 best = 0;
+    int lo = 0, hi = (int)vals.size() - 1;
+    while (lo <= hi) {
+        const int mid = lo + (hi - lo) / 2;
+        if (has_perfect_matching(S, R, vals[mid])) {
+            best = vals[mid];
+            lo = mid + 1;
+        } else {
+            hi = mid - 1;
+        }
+    }
+    return best;
+}
+
+int decompose_bottleneck(int S, const i64* Q, const i64* A, int cap, int32_t* stages, i64* bytes) {
+    std::vector<i64> R((size_t)S * S), Rreal((size_t)S * S);
+    i64 Lrem = 0;
+    for (int a = 0; a < S; ++a)
+        for (int d = 0; d < S; ++d) {
+            R[(size_t)a * S + d] = at(Q, S, a, d) + at(A, S, a, d);
+            Rreal[(size_t)a * S + d] = at(Q, S, a, d);
+            if (a == 0) Lrem += R[(size_t)a * S + d];
+        }
+    int s = 0;
+    while (Lrem > 0) {
+        if (s >= cap) return -2;
+        const i64 t = bottleneck_value(S, R);
+        if (t <= 0) return -3;
+        Matcher M(S, R, t);
+        for (int r0 = 0; r0 < S; ++r0)
+            if (!M.augment(r0)) return -3;
+        const i64 c = take_stage(S, M.mr, R, Rreal, stages + (size_t)s * S, bytes + (size_t)s * S);
+        Lrem -= c;
+        ++s;
+    }
+    return s;
 }
 
 // ---------------------------------------------------------------------------
@@ -668,6 +770,15 @@ int oracle_decompose(int S, const int64_t* Q, const int64_t* A, int cap, int32_t
     return decompose(S, Q, A, cap, stages, bytes);
 }
 
+int oracle_decompose_bottleneck(int S, const int64_t* Q, const int64_t* A, int cap,
+                                int32_t* stages, int64_t* bytes) {
+    return decompose_bottleneck(S, Q, A, cap, stages, bytes);
+}
+
+int64_t oracle_bottleneck_value(int S, const int64_t* R) {
+    return bottleneck_value(S, std::vector<i64>(R, R + (size_t)S * S));
+}
+
 void oracle_cost(int S, int G, double bw_up, double bw_out, double delay, const int64_t* T,
                  const int64_t* X, const int64_t* intra_out, const int64_t* intra_in, int K,
                  const int64_t* bytes, double* out4, double* extra3) {
@@ -691,10 +802,12 @@ int oracle_spreadout(int S, int G, double bw_up, double bw_out, double delay,
 // Whole path for one matrix.  stages/bytes hold `cap` stage rows of S entries;
 // rows >= K are left untouched.  *num_stages = K >= 0, -1 (negative entry),
 // -2 (cap exceeded), -3 (internal).  Q_out / A_out (S*S each) may be NULL.
+// bottleneck != 0 takes the stages from decompose_bottleneck() instead of decompose().
 int oracle_synthesize(int S, int G, double bw_up, double bw_out, double delay,
                       const int64_t* traffic,
                       int64_t* X, int32_t* stages, int64_t* bytes, int cap, int32_t* num_stages,
-                      double* out4, double* extra3, int64_t* Q_out, int64_t* A_out) {
+                      double* out4, double* extra3, int64_t* Q_out, int64_t* A_out,
+                      int bottleneck) {
     const int N = S * G;
     std::vector<i64> T((size_t)S * S), Q((size_t)S * S), A((size_t)S * S), io(N), ii(N);
     if (aggregate(S, G, traffic, T.data(), io.data(), ii.data()) != 0) {
@@ -704,7 +817,8 @@ int oracle_synthesize(int S, int G, double bw_up, double bw_out, double delay,
     rebalance(S, G, traffic, X);
     collapse(S, G, T.data(), Q.data());
     embed(S, Q.data(), A.data());
-    const int K = decompose(S, Q.data(), A.data(), cap, stages, bytes);
+    const int K = bottleneck ? decompose_bottleneck(S, Q.data(), A.data(), cap, stages, bytes)
+                             : decompose(S, Q.data(), A.data(), cap, stages, bytes);
     *num_stages = K;
     if (Q_out) std::memcpy(Q_out, Q.data(), sizeof(i64) * S * S);
     if (A_out) std::memcpy(A_out, A.data(), sizeof(i64) * S * S);

@@ -52,8 +52,13 @@ def _bind(path):
         L.oracle_cost.restype = None
         L.oracle_synthesize.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double,
                                         ctypes.c_double, ctypes.c_double, _i64p, _i64p, _i32p,
-                                        _i64p, ctypes.c_int, _i32p, _f64p, _f64p, _i64p, _i64p]
+                                        _i64p, ctypes.c_int, _i32p, _f64p, _f64p, _i64p, _i64p,
+                                        ctypes.c_int]
         L.oracle_synthesize.restype = ctypes.c_int
+        L.oracle_decompose_bottleneck.argtypes = L.oracle_decompose.argtypes
+        L.oracle_decompose_bottleneck.restype = ctypes.c_int
+        L.oracle_bottleneck_value.argtypes = [ctypes.c_int, _i64p]
+        L.oracle_bottleneck_value.restype = ctypes.c_int64
         L.oracle_spreadout.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double,
                                        ctypes.c_double, _i64p, _f64p]
         L.oracle_spreadout.restype = ctypes.c_int
@@ -162,7 +167,13 @@ def embed(Q):
     return int(L), A
 
 
-def decompose(Q, A, cap=None):
+def bottleneck_value(R):
+    """largest t such that the cells of R holding at least t contain a perfect matching"""
+    R = _c64(R)
+    return int(lib().oracle_bottleneck_value(R.shape[0], _p64(R)))
+
+
+def decompose(Q, A, cap=None, bottleneck=False):
     """-> (K, stages[K,S] int32, bytes[K,S] int64)"""
     Q = _c64(Q)
     A = _c64(A)
@@ -170,7 +181,8 @@ def decompose(Q, A, cap=None):
     cap = S * S if cap is None else cap
     st = np.full((max(cap, 1), S), -7, np.int32)
     by = np.full((max(cap, 1), S), -7, np.int64)
-    K = lib().oracle_decompose(S, _p64(Q), _p64(A), cap, _p32(st), _p64(by))
+    fn = lib().oracle_decompose_bottleneck if bottleneck else lib().oracle_decompose
+    K = fn(S, _p64(Q), _p64(A), cap, _p32(st), _p64(by))
     if K < 0:
         return K, st[:0], by[:0]
     return K, st[:K].copy(), by[:K].copy()
@@ -197,7 +209,7 @@ class Plan:
     __slots__ = ("status", "K", "X", "stages", "stage_bytes", "time4", "extra3", "Q", "A")
 
 
-def synthesize(S, G, bw_up, bw_out, traffic, cap=None, delay=0.0):
+def synthesize(S, G, bw_up, bw_out, traffic, cap=None, delay=0.0, bottleneck=False):
     N = S * G
     traffic = _c64(traffic).reshape(N, N)
     cap = S * S if cap is None else cap
@@ -210,7 +222,7 @@ def synthesize(S, G, bw_up, bw_out, traffic, cap=None, delay=0.0):
     Q = np.zeros((S, S), np.int64)
     A = np.zeros((S, S), np.int64)
     lib().oracle_synthesize(S, G, bw_up, bw_out, delay, _p64(traffic), _p64(X), _p32(st), _p64(by), cap,
-                            _p32(ns), _pf(out4), _pf(ex), _p64(Q), _p64(A))
+                            _p32(ns), _pf(out4), _pf(ex), _p64(Q), _p64(A), int(bottleneck))
     p = Plan()
     p.status = int(ns[0])
     p.K = max(int(ns[0]), 0)

@@ -10,6 +10,7 @@ import tempfile
 
 import pytest
 
+import test_oracle_bottleneck as TN
 import test_oracle_bruteforce as TB
 import test_oracle_build_traffic as TT
 import test_oracle_pins as TP
@@ -49,8 +50,8 @@ MUTATIONS = [
      "Rreal[(size_t)a * S + d] -= real;",
      ""),
     ("stage destination written for the column, not the row",
-     "stages[(size_t)s * S + a] = real > 0 ? d : -1;",
-     "stages[(size_t)s * S + a] = real > 0 ? M.mc[a] : -1;"),
+     "stage_row[a] = real > 0 ? d : -1;",
+     "stage_row[d] = real > 0 ? a : -1;"),
     ("balance term divided by the scale-out bandwidth",
      "const double t0 = (double)bal / bw_up;",
      "const double t0 = (double)bal / bw_out;"),
@@ -100,6 +101,18 @@ MUTATIONS = [
     ("intra-server portion serialised before the first stage",
      "double out_end = t, up_free = t;\n    if (intra > 0) up_free = t + (delay + (double)intra / bw_up);",
      "if (intra > 0) t = t + (delay + (double)intra / bw_up);\n    double out_end = t, up_free = t;"),
+    ("bottleneck search walks down after a success",
+     "best = vals[mid];\n            lo = mid + 1;",
+     "best = vals[mid];\n            hi = mid - 1;"),
+    ("threshold graph drops the cells that hold exactly the threshold",
+     "if (R[(size_t)a * S + d] < t || seen[d]) continue;",
+     "if (R[(size_t)a * S + d] <= t || seen[d]) continue;"),
+    ("fewer-stages variant matches on the support instead of the threshold graph",
+     "Matcher M(S, R, t);",
+     "Matcher M(S, R);"),
+    ("canonical search treats its threshold as exclusive",
+     "if (inF[a] && R[(size_t)a * S + d] >= thr) {",
+     "if (inF[a] && R[(size_t)a * S + d] > thr) {"),
 ]
 
 
@@ -132,6 +145,10 @@ def battery(O):
     TR.test_pipeline_hand_example(O)
     TR.test_pipeline_hides_everything_but_the_last_redistribution(O)
     TR.test_pipeline_scale_up_chain_when_nothing_hides(O)
+    TN.test_bottleneck_value_is_the_best_over_all_permutations(O, 4)
+    TN.test_hand_example(O)
+    TN.test_stage_by_stage_replay_on_matrices_without_virtual_bytes(O, 4, 7)
+    TN.test_invariants_with_virtual_bytes(O, 5, "small")
 
 
 def test_battery_passes_on_the_real_oracle(oracle):
