@@ -53,14 +53,11 @@
 #include <limits>
 #include <type_traits>
 
-#include "k1_rebalance.hpp"
+#include "matching.hpp"
 
 namespace fastk {
 
-typedef unsigned int u32;
-
 constexpr int K2_THREADS = 64;
-constexpr u64 VFLAG = 1ull << 63;      // LDS word flag: the cell holds virtual bytes
 
 // R[S][S], column deficit intervals PC[S], EC[S], frontier history [(S+2)][2]
 __host__ __device__ inline size_t k2_lds_data_bytes(int S) {
@@ -69,71 +66,6 @@ __host__ __device__ inline size_t k2_lds_data_bytes(int S) {
 // ... plus one spare word per lane slot and one in front: the lane slots that hold no row
 // (S below 64 * NR) read and write there, so the per-stage reload needs no bounds predicate
 inline size_t k2_lds_bytes(int S) { return k2_lds_data_bytes(S) + (size_t)(2 * 64 + 1) * 8; }
-
-__device__ __forceinline__ u64 ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
-__device__ __forceinline__ u32 rdl(u32 v, int lane) { return (u32)__builtin_amdgcn_readlane(v, lane); }
-__device__ __forceinline__ u64 rdl64(u64 v, int lane) {
-    return ((u64)rdl((u32)(v >> 32), lane) << 32) | rdl((u32)v, lane);
-}
-
-// tells the compiler that a value is the same in every lane
-__device__ __forceinline__ u64 uniform64(u64 x) {
-    return ((u64)(u32)__builtin_amdgcn_readfirstlane((u32)(x >> 32)) << 32) |
-           (u64)(u32)__builtin_amdgcn_readfirstlane((u32)x);
-}
-
-// min over the 64 lanes (all lanes must be active), result wave-uniform
-__device__ __forceinline__ u32 wave_min_u32(u32 v) {
-    asm volatile(
-        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
-        "s_nop 1\n\tv_min_u32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-        "s_nop 1"
-        : "+v"(v));
-    return rdl(v, 63);
-}
-__device__ __forceinline__ u64 wave_min_u64(u64 x) {
-    const u32 hi = (u32)(x >> 32);
-    const u64 small = ballot(hi == 0);
-    if (small) {      // some value fits 32 bits: the minimum is among those
-        const u32 lo = hi == 0 ? (u32)x : 0xFFFFFFFFu;
-        return wave_min_u32(lo);
-    }
-    const u32 mhi = wave_min_u32(hi);
-    const u32 lo = hi == mhi ? (u32)x : 0xFFFFFFFFu;
-    const u32 mlo = wave_min_u32(lo);
-    return ((u64)mhi << 32) | mlo;
-}
-// v[lane] = val for one lane; val and lane are wave-uniform
-__device__ __forceinline__ void wrlane(u32& v, u32 val, int lane) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0"
-                 : "+v"(v) : "s"(val), "s"(lane));
-}
-__device__ __forceinline__ void wrlane64(u64& v, u64 val, int lane) {
-    u32 lo = (u32)v, hi = (u32)(v >> 32);
-    asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\tv_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
-                 : "+v"(lo), "+v"(hi) : "s"((u32)val), "s"((u32)(val >> 32)), "s"(lane));
-    v = ((u64)hi << 32) | lo;
-}
-__device__ __forceinline__ i64 wave_max_i64(i64 v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const i64 o = __shfl_xor(v, off, 64);
-        v = o > v ? o : v;
-    }
-    return v;
-}
-__device__ __forceinline__ i64 wave_scan_incl(i64 v, int lane) {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const i64 o = __shfl_up(v, off, 64);
-        if (lane >= off) v += o;
-    }
-    return v;
-}
 
 // NR = rows (and columns) per lane: 1 for S <= 64, 2 for S <= 128.
 // NR: rows and columns per lane; FULL: S == 64 * NR, every lane slot holds a real row (the
@@ -151,88 +83,12 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     const int b = blockIdx.x;
     const int lane = threadIdx.x;
 
-    {
-        int bad = 0;
-        for (int a = lane; a < S; a += 64) bad |= (int)wsPart[((size_t)b * S + a) * K1_PART + 2];
-        if (ballot(bad != 0)) {
-            if (lane == 0) out_num[b] = -1;
-            return;
-        }
-    }
-    const i64* Qg = wsQ + (size_t)b * S * S;
-    for (int e = lane; e < S * S; e += 64) R[e] = (u64)Qg[e];
-    __syncthreads();
-
-    i64 rsum[NR], csum[NR];
-#pragma unroll
-    for (int k = 0; k < NR; ++k) {
-        const int x = lane + 64 * k;
-        rsum[k] = 0;
-        csum[k] = 0;
-        if (x < S) {
-            for (int j = 0; j < S; ++j) {
-                int d = j + x;
-                d = d >= S ? d - S : d;
-                rsum[k] += (i64)R[(size_t)x * S + d];
-                csum[k] += (i64)R[(size_t)j * S + x];
-            }
-        }
-    }
-    i64 lmax = 0;
-#pragma unroll
-    for (int k = 0; k < NR; ++k) lmax = max(lmax, max(rsum[k], csum[k]));
-    const i64 L = (i64)uniform64((u64)wave_max_i64(lmax));
-    if (L == 0) {
-        if (lane == 0) out_num[b] = 0;
+    i64 diag[NR], PR[NR], ER[NR];
+    const i64 L = embed_into_lds<NR>(wsQ, wsPart, b, S, lane, R, PC, EC, diag, PR, ER);
+    if (L <= 0) {
+        if (lane == 0) out_num[b] = (int32_t)L;     // -1: invalid input, 0: nothing to send
         return;
     }
-
-    i64 diag[NR], PR[NR], ER[NR];
-    {
-        i64 dr[NR], dc[NR];
-#pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            const int x = lane + 64 * k;
-            dr[k] = x < S ? L - rsum[k] : 0;
-            dc[k] = x < S ? L - csum[k] : 0;
-            diag[k] = min(dr[k], dc[k]);
-            dr[k] -= diag[k];
-            dc[k] -= diag[k];
-        }
-        i64 base_r = 0, base_c = 0;
-#pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            const int x = lane + 64 * k;
-            const i64 ir = wave_scan_incl(dr[k], lane);
-            const i64 ic = wave_scan_incl(dc[k], lane);
-            PR[k] = base_r + ir - dr[k];
-            ER[k] = base_r + ir;
-            if (x < S) {
-                PC[x] = base_c + ic - dc[k];
-                EC[x] = base_c + ic;
-            }
-            base_r += __shfl(ir, 63, 64);
-            base_c += __shfl(ic, 63, 64);
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < NR; ++k) {
-        const int x = lane + 64 * k;
-        if (x < S) {
-            if (diag[k] > 0) R[(size_t)x * S + x] = (R[(size_t)x * S + x] + (u64)diag[k]) | VFLAG;
-            if (ER[k] > PR[k]) {
-                for (int j = 0; j < S; ++j) {
-                    int d = j + x;
-                    d = d >= S ? d - S : d;
-                    const i64 l = max(PR[k], PC[d]);
-                    const i64 h = min(ER[k], EC[d]);
-                    if (h > l) R[(size_t)x * S + d] = (R[(size_t)x * S + d] + (u64)(h - l)) | VFLAG;
-                }
-            }
-        }
-    }
-    __syncthreads();
 
     // support masks: bit a of cm[k][a/64] set while R[a][column lane+64k] > 0
     u64 cm[NR][NR];
@@ -322,115 +178,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         };
 
         auto augment = [&](int r0) -> bool {
-            u64 F[NR], VIS[NR];
-#pragma unroll
-            for (int w = 0; w < NR; ++w) {
-                F[w] = (r0 >> 6) == w ? 1ull << (r0 & 63) : 0;
-                VIS[w] = 0;
-            }
-            int nfree = 0;
-#pragma unroll
-            for (int w = 0; w < NR; ++w) nfree += __builtin_popcountll(FREEC[w]);
-            const bool few = nfree <= 2;
-            int level = 1, dstar = -1, a = -1;
-            for (;;) {
-                if (few) {
-                    // few unmatched columns: test each against the frontier with scalar work
-                    u64 fr[NR];
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) fr[w] = FREEC[w];
-                    while (any(fr)) {
-                        const int f = lowest(fr);
-                        u64 cmf[NR];
-                        col_mask(f, cmf);
-#pragma unroll
-                        for (int w = 0; w < NR; ++w) cmf[w] &= F[w];
-                        if (any(cmf)) {
-                            dstar = f;
-                            a = lowest(cmf);
-                            break;
-                        }
-#pragma unroll
-                        for (int w = 0; w < NR; ++w)
-                            if ((f >> 6) == w) fr[w] &= ~(1ull << (f & 63));
-                    }
-                    if (dstar >= 0) break;
-                }
-                u64 N[NR];
-#pragma unroll
-                for (int k = 0; k < NR; ++k) {
-                    u64 cand = 0;
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) cand |= cm[k][w] & F[w];
-                    N[k] = ballot(cand != 0) & ~VIS[k];
-                }
-                if (!few) {
-                    u64 fr[NR];
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) fr[w] = N[w] & FREEC[w];
-                    if (any(fr)) {
-                        dstar = lowest(fr);
-                        u64 cmf[NR];
-                        col_mask(dstar, cmf);
-#pragma unroll
-                        for (int w = 0; w < NR; ++w) cmf[w] &= F[w];
-                        a = lowest(cmf);
-                        break;
-                    }
-                }
-                if (!any(N)) return false;
-#pragma unroll
-                for (int w = 0; w < NR; ++w) VIS[w] |= N[w];
-                if (level >= 2 && lane == 0) {
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) Fh[level * 2 + w] = F[w];
-                }
-#pragma unroll
-                for (int k = 0; k < NR; ++k) {
-                    const int m = mr[k];
-                    u64 word;
-                    if constexpr (NR == 2) word = m < 64 ? N[0] : N[1];
-                    else word = N[0];
-                    F[k] = ballot(m >= 0 && ((word >> (m & 63)) & 1));
-                }
-                ++level;
-            }
-            // flip the path: column dstar <- row a <- its old column <- ... <- r0
-            int d = dstar;
-            for (int hops = 0;; ++hops) {
-                if (hops > S) return false;
-                int prev;
-                if constexpr (NR == 2) prev = (a >> 6) ? (int)rdl(mr[1], a & 63) : (int)rdl(mr[0], a & 63);
-                else prev = (int)rdl(mr[0], a & 63);
-#pragma unroll
-                for (int k = 0; k < NR; ++k) {
-                    mr[k] = (lane + 64 * k == a) ? d : mr[k];
-                }
-                if (a == r0) break;
-                d = prev;
-                --level;
-                u64 Fl[NR];
-                if (level == 1) {
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) Fl[w] = (r0 >> 6) == w ? 1ull << (r0 & 63) : 0;
-                } else {
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) {
-                        const u64 x = Fh[level * 2 + w];
-                        Fl[w] = ((u64)(u32)__builtin_amdgcn_readfirstlane((u32)(x >> 32)) << 32) |
-                                (u64)(u32)__builtin_amdgcn_readfirstlane((u32)x);
-                    }
-                }
-                u64 cmd[NR];
-                col_mask(d, cmd);
-#pragma unroll
-                for (int w = 0; w < NR; ++w) cmd[w] &= Fl[w];
-                a = lowest(cmd);
-            }
-#pragma unroll
-            for (int w = 0; w < NR; ++w)
-                if ((dstar >> 6) == w) FREEC[w] &= ~(1ull << (dstar & 63));
-            return true;
+            return bfs_augment<NR>(r0, cm, mr, FREEC, Fh, S, lane);
         };
 
         // Make rv / rl describe the cell each row is matched to now.  Loads are
