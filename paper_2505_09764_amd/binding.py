@@ -22,7 +22,7 @@ FAST_STATUS_STAGE_OVERFLOW = -2
 FAST_STATUS_INTERNAL = -3
 
 EXPORTS = ("fast_plan_create", "fast_plan_max_stages", "fast_synthesize_batched",
-           "fast_plan_set_wakeup_delay", "fast_spreadout_batched", "fast_build_traffic_batched",
+           "fast_plan_set_wakeup_delay", "fast_plan_set_matching", "fast_spreadout_batched", "fast_build_traffic_batched",
            "fast_stage_order_batched", "fast_stage_offsets_batched",
            "fast_redistribution_batched", "fast_redistribution_matrices",
            "fast_pipeline_time_batched",
@@ -57,6 +57,8 @@ def lib():
         L.fast_synthesize_batched.restype = ctypes.c_int
         L.fast_plan_set_wakeup_delay.argtypes = [vp, ctypes.c_double]
         L.fast_plan_set_wakeup_delay.restype = ctypes.c_int
+        L.fast_plan_set_matching.argtypes = [vp, ctypes.c_int]
+        L.fast_plan_set_matching.restype = ctypes.c_int
         L.fast_spreadout_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp]
         L.fast_spreadout_batched.restype = ctypes.c_int
         L.fast_stage_order_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp]
@@ -113,6 +115,16 @@ def fast_plan_set_wakeup_delay(plan, seconds):
     rc = lib().fast_plan_set_wakeup_delay(plan, float(seconds))
     if rc != FAST_OK:
         raise FastError("fast_plan_set_wakeup_delay", rc)
+
+
+FAST_MATCHING_SUPPORT = 0
+FAST_MATCHING_BOTTLENECK = 1
+
+
+def fast_plan_set_matching(plan, matching):
+    rc = lib().fast_plan_set_matching(plan, int(matching))
+    if rc != FAST_OK:
+        raise FastError("fast_plan_set_matching", rc)
 
 
 def fast_spreadout_batched(plan, B, traffic, out_spreadout_time, stream):
@@ -247,6 +259,11 @@ class Synthesizer:
 
     def set_wakeup_delay(self, seconds):
         fast_plan_set_wakeup_delay(self.plan, seconds)
+
+    def set_matching(self, matching):
+        """"support" (the paper's rule) or "bottleneck" (fewer, larger stages)."""
+        code = {"support": FAST_MATCHING_SUPPORT, "bottleneck": FAST_MATCHING_BOTTLENECK}.get(matching, matching)
+        fast_plan_set_matching(self.plan, code)
 
     def spreadout(self, traffic, out=None):
         """SpreadOut baseline times -> float64 tensor [B, 2] (GPU level, server level)."""

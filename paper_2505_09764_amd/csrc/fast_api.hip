@@ -10,6 +10,7 @@
 
 #include "k1_rebalance.hpp"
 #include "k2_birkhoff.hpp"
+#include "k9_bottleneck.hpp"
 #include "k3_cost.hpp"
 #include "k4_spreadout.hpp"
 #include "k5_build_traffic.hpp"
@@ -23,6 +24,7 @@ struct fast_plan {
     int S, G;
     double bw_up, bw_out;
     double delay;  // link wake-up delay per executed step, seconds
+    int matching;  // FAST_MATCHING_*: which decomposition kernel the synthesis call runs
     int device;
     int max_stages;
     // device workspace for `cap_B` matrices
@@ -151,6 +153,9 @@ k2_fn k2_kernel(int S) {
     if (S == 64) return &fastk::k2_birkhoff<1, true>;
     return &fastk::k2_birkhoff<1, false>;
 }
+k2_fn k9_kernel(int S) {
+    return S > 64 ? &fastk::k9_bottleneck<2> : &fastk::k9_bottleneck<1>;
+}
 
 // The stage-walk kernel: with or without pair lists, with or without a stage order, and the
 // variant without store predicates when S is a multiple of its 64 source servers per wavefront.
@@ -198,6 +203,7 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     p->device = dev;
     p->max_stages = S * S;
     p->delay = 0.0;
+    p->matching = FAST_MATCHING_SUPPORT;
     p->cap_B = 0;
     p->wsT = p->wsQ = p->wsPart = p->wsC = nullptr;
     p->spo_cap_B = 0;
@@ -222,6 +228,10 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     if (lds2 > 48 * 1024)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2_kernel(S)),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds2);
+    if (e == hipSuccess && fastk::k9_lds_bytes(S) > 48 * 1024)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k9_kernel(S)),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)fastk::k9_lds_bytes(S));
     if (e == hipSuccess && link_bw_up < (double)(G - 1) * link_bw_out)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::k3_cost),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -284,11 +294,15 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
     }
     if (ev) (void)hipEventRecord(ev[1], stream);
 
-    const size_t lds2 = fastk::k2_lds_bytes(p->S);
     i64* sb = reinterpret_cast<i64*>(out_stage_bytes);
-    hipLaunchKernelGGL(k2_kernel(p->S), dim3(B), dim3(fastk::K2_THREADS),
-                       lds2, stream, p->wsQ, p->wsPart, out_stages, sb, out_num_stages, p->wsC, p->S,
-                       p->max_stages);
+    if (p->matching == FAST_MATCHING_BOTTLENECK)
+        hipLaunchKernelGGL(k9_kernel(p->S), dim3(B), dim3(fastk::K9_THREADS),
+                           fastk::k9_lds_bytes(p->S), stream, p->wsQ, p->wsPart, out_stages, sb,
+                           out_num_stages, p->wsC, p->S, p->max_stages);
+    else
+        hipLaunchKernelGGL(k2_kernel(p->S), dim3(B), dim3(fastk::K2_THREADS),
+                           fastk::k2_lds_bytes(p->S), stream, p->wsQ, p->wsPart, out_stages, sb,
+                           out_num_stages, p->wsC, p->S, p->max_stages);
     if (ev) (void)hipEventRecord(ev[2], stream);
 
     const bool slow_up = p->bw_up < (double)(p->G - 1) * p->bw_out;
@@ -309,6 +323,13 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
 int fast_plan_set_wakeup_delay(fast_plan_t* p, double seconds) {
     if (!p || !std::isfinite(seconds) || seconds < 0.0) return FAST_ERR_INVALID_ARG;
     p->delay = seconds;
+    return FAST_OK;
+}
+
+int fast_plan_set_matching(fast_plan_t* p, int matching) {
+    if (!p || (matching != FAST_MATCHING_SUPPORT && matching != FAST_MATCHING_BOTTLENECK))
+        return FAST_ERR_INVALID_ARG;
+    p->matching = matching;
     return FAST_OK;
 }
 

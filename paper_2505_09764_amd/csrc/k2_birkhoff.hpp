@@ -111,17 +111,7 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     // residual matrix is repacked in place (flag in bit 31) and every per-stage subtraction,
     // comparison and select is one instruction instead of two.
     const bool narrow = L < ((i64)1 << 31);
-    if (narrow) {
-        u32* R32 = reinterpret_cast<u32*>(k2_smem);
-        for (int e0 = 0; e0 < S * S; e0 += 64) {
-            const int e = e0 + lane;
-            u64 v = 0;
-            if (e < S * S) v = R[e];
-            __syncthreads();                    // chunk read before its (lower) words are rewritten
-            if (e < S * S) R32[e] = (u32)v | ((v & VFLAG) ? 0x80000000u : 0u);
-        }
-        __syncthreads();
-    }
+    if (narrow) repack_narrow(R, S, lane);
     auto run = [&](auto tag) {
         typedef decltype(tag) V;                // word type of the residuals
         typedef std::make_signed_t<V> SV;

@@ -192,6 +192,20 @@ __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
     return L;
 }
 
+// No residual exceeds L, the largest line sum: when L < 2^31 the 64-bit words of R (S*S of them,
+// flag in bit 63) are repacked in place to 32-bit words (flag in bit 31).
+__device__ __forceinline__ void repack_narrow(u64* R, int S, int lane) {
+    u32* R32 = reinterpret_cast<u32*>(R);
+    for (int e0 = 0; e0 < S * S; e0 += 64) {
+        const int e = e0 + lane;
+        u64 v = 0;
+        if (e < S * S) v = R[e];
+        __syncthreads();                    // chunk read before its (lower) words are rewritten
+        if (e < S * S) R32[e] = (u32)v | ((v & VFLAG) ? 0x80000000u : 0u);
+    }
+    __syncthreads();
+}
+
 // Canonical augmenting search from the unmatched row r0 (wave-uniform) on the graph given by
 // the column masks cm (bit a of cm[k][a / 64] set while cell (a, column lane + 64k) is an
 // edge): level-synchronous, the lowest-numbered frontier row becomes the parent of a newly

@@ -61,6 +61,7 @@ def test_argument_checks_without_device(fastlib):
     # every other entry point rejects a missing plan before anything else
     E = b.FAST_ERR_INVALID_ARG
     assert fastlib.fast_plan_set_wakeup_delay(None, 0.0) == E
+    assert fastlib.fast_plan_set_matching(None, 0) == E
     assert fastlib.fast_spreadout_batched(None, 1, None, None, None) == E
     assert fastlib.fast_stage_order_batched(None, 1, None, None, None, None) == E
     assert fastlib.fast_build_traffic_batched(None, 1, 1, None, None, 1, None, None, None) == E

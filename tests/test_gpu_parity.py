@@ -31,13 +31,15 @@ def torch_cuda():
     return torch
 
 
-def run_gpu(torch, S, G, bw_up, bw_out, traffic, prefill=True):
+def run_gpu(torch, S, G, bw_up, bw_out, traffic, prefill=True, matching=None):
     """traffic: numpy [B,N,N] or device tensor.  Returns host numpy outputs."""
     from paper_2505_09764_amd.binding import Synthesizer
     dev = torch.device("cuda:0")
     t = traffic if isinstance(traffic, torch.Tensor) else torch.from_numpy(
         np.ascontiguousarray(traffic, dtype=np.int64)).to(dev)
     syn = Synthesizer(S, G, bw_up, bw_out, dev)
+    if matching is not None:
+        syn.set_matching(matching)
     out = syn.alloc_outputs(t.shape[0])
     if prefill:
         out.rebalance.fill_(SENT64)
@@ -54,8 +56,8 @@ def run_gpu(torch, S, G, bw_up, bw_out, traffic, prefill=True):
     return res
 
 
-def compare_one(oracle, S, G, bw_up, bw_out, tr, res, b, check_untouched=True):
-    p = oracle.synthesize(S, G, bw_up, bw_out, tr)
+def compare_one(oracle, S, G, bw_up, bw_out, tr, res, b, check_untouched=True, bottleneck=False):
+    p = oracle.synthesize(S, G, bw_up, bw_out, tr, bottleneck=bottleneck)
     K = int(res["K"][b])
     assert K == p.status, f"matrix {b}: stage count / status {K} != oracle {p.status}"
     if K < 0:
@@ -69,11 +71,12 @@ def compare_one(oracle, S, G, bw_up, bw_out, tr, res, b, check_untouched=True):
     return p
 
 
-def compare_batch(oracle, w_S, w_G, bw_up, bw_out, traffic, res, idx=None, threads=8):
+def compare_batch(oracle, w_S, w_G, bw_up, bw_out, traffic, res, idx=None, threads=8,
+                  bottleneck=False):
     idx = range(traffic.shape[0]) if idx is None else idx
     with ThreadPoolExecutor(threads) as ex:
-        list(ex.map(lambda b: compare_one(oracle, w_S, w_G, bw_up, bw_out, traffic[b], res, b),
-                    idx))
+        list(ex.map(lambda b: compare_one(oracle, w_S, w_G, bw_up, bw_out, traffic[b], res, b,
+                                          bottleneck=bottleneck), idx))
 
 
 # ----------------------------------------------------------------------------

@@ -40,7 +40,7 @@ def _random_traffic(rng, B, S, G, kind):
 
 
 def _check(oracle, torch, S, G, bw_up, bw_out, t_host, delay=0.0, all_matrices=True, sel_per=3,
-           seed=0):
+           seed=0, matching=None):
     from paper_2505_09764_amd.binding import Synthesizer
     dev = torch.device("cuda:0")
     B = t_host.shape[0]
@@ -48,6 +48,8 @@ def _check(oracle, torch, S, G, bw_up, bw_out, t_host, delay=0.0, all_matrices=T
     syn = Synthesizer(S, G, bw_up, bw_out, dev)
     if delay:
         syn.set_wakeup_delay(delay)
+    if matching is not None:
+        syn.set_matching(matching)
     out = syn.synthesize(t)
     order = syn.stage_order(out)
     Ks = out.num_stages.cpu().numpy()
