@@ -17,6 +17,8 @@ quoted on.  Prints ONE JSON line:
   spreadout_baseline  time of the SpreadOut comparison pass and predicted-time ratios
   pipeline_analysis   time of stage order + exact redistribution volumes + pipelined completion
                       time of the same plans, and how they compare with the serial model
+  fewer_stages_variant  the same batch with a bottleneck assignment per stage
+                      (fast_plan_set_matching): stage count and time of its decomposition kernel
 """
 import argparse
 import json
@@ -211,6 +213,26 @@ def main():
             "mean_T_pipeline_exact_over_t_opt": float((peh[:, 0] / tp[:, 3]).mean()),
             "exact_over_worstcase_redistribution_bytes": exact / worst if worst else None}
 
+    # The same batch with the fewer-stages rule (a bottleneck assignment per stage)
+    synb = binding.Synthesizer(S, G, w.bw_up, w.bw_out, dev)
+    synb.set_matching("bottleneck")
+    outb = synb.alloc_outputs(B)
+    nb = max(2, min(args.steps, 3))
+    _, sb_ms, kb_ms, _ = time_steps(torch, synb, traffic, outb, nb, 1, True)
+    Kb = outb.num_stages.cpu().numpy()
+    orderb = synb.stage_order(outb)
+    _, rbb = synb.redistribution(traffic, outb, orderb)
+    peb = synb.pipeline_time(outb, orderb, rbb).cpu().numpy()
+    tpb = outb.predicted_time.cpu().numpy()
+    fewer = {"stages_per_schedule_mean": float(Kb.mean()),
+             "stages_vs_default": float(Kb.sum()) / max(int(K.sum()), 1),
+             "ms_per_call": sum(sb_ms) / len(sb_ms),
+             "k9_bottleneck_ms": sum(k[1] for k in kb_ms) / len(kb_ms),
+             "us_per_stage": sum(k[1] for k in kb_ms) / len(kb_ms) * 1e3 / max(int(Kb.max()), 1),
+             "mean_T_fast_over_t_opt": float((tpb[:, 0] / tpb[:, 3]).mean()),
+             "mean_T_pipeline_exact_over_t_opt": float((peb[:, 0] / tpb[:, 3]).mean())}
+    synb.close()
+
     cpu = None
     if not args.no_cpu:
         host = traffic[:32].cpu().numpy()
@@ -248,6 +270,7 @@ def main():
         "latency_b1": lat,
         "spreadout_baseline": spo,
         "pipeline_analysis": pipe,
+        "fewer_stages_variant": fewer,
         "cpu_baseline": cpu,
     }
     syn.close()

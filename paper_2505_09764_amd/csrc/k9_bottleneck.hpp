@@ -28,9 +28,16 @@
 //      has no real bytes left are idle (-1); the matched cells lose c in LDS.
 //
 // One wavefront per matrix; lane l owns rows and columns l, l + 64.  The residual matrix is
-// always current in LDS (64-bit words, or 32-bit when no line sum reaches 2^31); the virtual
-// part of a cell is recomputed from the embedding's prefix-sum intervals when the cell is
-// flagged.  Outputs and status codes as kernel 2.
+// always current in LDS (64-bit words, or 32-bit when no line sum reaches 2^31) and carries no
+// flag bits: the virtual part of a matched cell is recomputed from the embedding's prefix-sum
+// intervals when the stage is emitted.  The pass that builds the masks is the inner loop
+// (S*S cells per probe, 5 to 6 probes per stage): it reads 32-bit words only - in 64-bit mode
+// the low halves, with the few cells of 2^32 and more (virtual bytes piled on the diagonal)
+// kept as one more mask per column that is simply OR-ed in, valid while t < 2^32 - and spends
+// three VALU instructions per cell: t-1-v with borrow = (v >= t), the running minimum of that
+// difference (the largest value under t, from which the next upper bound comes; low halves of
+// the large cells may enter it, which can only make that bound less tight), and an
+// add-with-carry that shifts the borrow into the mask.  Outputs and status codes as kernel 2.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -71,13 +78,19 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         return;
     }
     const bool narrow = L < ((i64)1 << 31);
-    if (narrow) repack_narrow(R, S, lane);
+    if (narrow) {
+        repack_narrow<false>(R, S, lane);
+    } else {
+        for (int e = lane; e < S * S; e += 64) R[e] &= ~VFLAG;
+        __syncthreads();
+    }
 
     auto run = [&](auto tag) {
         typedef decltype(tag) V;                // word type of the residuals
-        constexpr V VF = (V)((V)1 << (sizeof(V) * 8 - 1));   // the cell holds virtual bytes
-        constexpr V VMAX = (V)~VF;                            // larger than any residual
+        constexpr bool WIDE = sizeof(V) == 8;
+        constexpr V VMAX = ~(V)0;               // larger than any residual
         V* Rv = reinterpret_cast<V*>(k9_smem);
+        const u32* R32 = reinterpret_cast<const u32*>(k9_smem);
         auto wave_min = [&](V v) -> V {
             if constexpr (sizeof(V) == 4) return wave_min_u32(v);
             else return wave_min_u64(v);
@@ -96,6 +109,7 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         int mr[NR];
         u64 ALLC[NR], FREEC[NR];
         u64 cm[NR][NR];
+        u64 big[NR][NR];        // 64-bit mode: the cells of the column that hold 2^32 or more
 #pragma unroll
         for (int k = 0; k < NR; ++k) {
             row[k] = lane + 64 * k;
@@ -104,40 +118,129 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             mr[k] = -1;
             const int n = S - 64 * k;
             ALLC[k] = n >= 64 ? ~0ull : (n <= 0 ? 0ull : ((1ull << n) - 1));
+#pragma unroll
+            for (int w = 0; w < NR; ++w) big[k][w] = 0;
+            if constexpr (WIDE) {
+                if (valid[k]) {
+                    for (int a = 0; a < S; ++a) {
+                        const u64 isbig = (Rv[(size_t)a * S + row[k]] >> 32) != 0;
+#pragma unroll
+                        for (int w = 0; w < NR; ++w)
+                            if ((a >> 6) == w) big[k][w] |= isbig << (a & 63);
+                    }
+                }
+            }
         }
 
         // Column masks of the graph {R >= t}: bit a of cm[k][a / 64] for cell (a, column
-        // lane + 64k).  Returns, per lane, the largest cell value below t seen in its columns.
+        // lane + 64k).  Returns, per lane, an upper bound on the cell values below t seen in its
+        // columns that is itself below t (the largest such value, unless a low half of a large
+        // cell comes in), 0 if there is none.
         auto build = [&](V t) -> V {
-            V below = 0;
+            if (!WIDE || t <= (V)0xFFFFFFFFu) {
+                // 32-bit words (the low halves in 64-bit mode: stride 2)
+                constexpr int ST = WIDE ? 2 : 1;
+                const u32 tm1 = (u32)t - 1u;
+                // smallest t-1-v over the cells with v < t, kept in four independent chains
+                u32 dm0 = 0xFFFFFFFFu, dm1 = 0xFFFFFFFFu, dm2 = 0xFFFFFFFFu, dm3 = 0xFFFFFFFFu;
 #pragma unroll
-            for (int k = 0; k < NR; ++k) {
-                const int x = min(row[k], S - 1);       // lanes past S re-read the last column
-#pragma unroll
-                for (int w = 0; w < NR; ++w) cm[k][w] = 0;
-                for (int a0 = 0; a0 < S; a0 += 32) {
-                    const int n = min(32, S - a0);
-                    u32 m = 0;
-                    const V* col = Rv + (size_t)a0 * S + x;
-#pragma unroll 8
-                    for (int i = 0; i < n; ++i) {
-                        const V v = col[(size_t)i * S] & (V)~VF;
-                        const bool ge = v >= t;
-                        m |= (u32)ge << i;
-                        const V u = ge ? (V)0 : v;
-                        below = u > below ? u : below;
-                    }
-                    const u64 part = (u64)m << (a0 & 32);
-#pragma unroll
-                    for (int w = 0; w < NR; ++w)
-                        if ((a0 >> 6) == w) cm[k][w] |= part;
-                }
-                if (!valid[k]) {
+                for (int k = 0; k < NR; ++k) {
+                    const int x = min(row[k], S - 1);       // lanes past S re-read the last column
 #pragma unroll
                     for (int w = 0; w < NR; ++w) cm[k][w] = 0;
+                    for (int a0 = 0; a0 < S; a0 += 32) {
+                        const u32* col = R32 + ((size_t)a0 * S + x) * ST;
+                        u32 m;
+                        if (a0 + 32 <= S) {
+                            // Four groups of eight rows, each with its own mask and minimum, so
+                            // that no instruction waits for the one before it; rows in descending
+                            // order, every step shifting its group's mask left by one.  The borrow
+                            // of each subtraction goes through a scalar register pair of its own
+                            // (a carry needs two instructions between its producer and consumer).
+                            u32 m0 = 0, m1 = 0, m2 = 0, m3 = 0;
+                            auto step4 = [&](u32 v0, u32 v1, u32 v2, u32 v3) {
+                                u32 d0, d1, d2, d3;
+                                u64 c0, c1, c2, c3;
+                                asm volatile(
+                                    "v_sub_co_u32_e64 %0, %4, %16, %17\n\t"
+                                    "v_sub_co_u32_e64 %1, %5, %16, %18\n\t"
+                                    "v_sub_co_u32_e64 %2, %6, %16, %19\n\t"
+                                    "v_sub_co_u32_e64 %3, %7, %16, %20\n\t"
+                                    "v_min_u32_e32 %8, %0, %8\n\t"
+                                    "v_min_u32_e32 %9, %1, %9\n\t"
+                                    "v_min_u32_e32 %10, %2, %10\n\t"
+                                    "v_min_u32_e32 %11, %3, %11\n\t"
+                                    "v_addc_co_u32_e64 %12, %4, %12, %12, %4\n\t"
+                                    "v_addc_co_u32_e64 %13, %5, %13, %13, %5\n\t"
+                                    "v_addc_co_u32_e64 %14, %6, %14, %14, %6\n\t"
+                                    "v_addc_co_u32_e64 %15, %7, %15, %15, %7"
+                                    : "=&v"(d0), "=&v"(d1), "=&v"(d2), "=&v"(d3),
+                                      "=&s"(c0), "=&s"(c1), "=&s"(c2), "=&s"(c3),
+                                      "+v"(dm0), "+v"(dm1), "+v"(dm2), "+v"(dm3),
+                                      "+v"(m0), "+v"(m1), "+v"(m2), "+v"(m3)
+                                    : "v"(tm1), "v"(v0), "v"(v1), "v"(v2), "v"(v3));
+                            };
+#pragma unroll
+                            for (int h = 4; h >= 0; h -= 4) {
+                                u32 w16[4][4];
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                                    for (int g = 0; g < 4; ++g)
+                                        w16[j][g] = col[(size_t)(8 * g + h + j) * S * ST];
+#pragma unroll
+                                for (int j = 3; j >= 0; --j)
+                                    step4(w16[j][0], w16[j][1], w16[j][2], w16[j][3]);
+                            }
+                            m = m0 | (m1 << 8) | (m2 << 16) | (m3 << 24);
+                        } else {
+                            m = 0;
+                            for (int i = S - a0 - 1; i >= 0; --i) {
+                                const u32 v = col[(size_t)i * S * ST];
+                                u32 d;
+                                asm volatile("v_sub_co_u32_e32 %0, vcc, %3, %4\n\t"
+                                             "v_min_u32_e32 %1, %0, %1\n\t"
+                                             "s_nop 0\n\t"
+                                             "v_addc_co_u32_e32 %2, vcc, %2, %2, vcc"
+                                             : "=&v"(d), "+v"(dm0), "+v"(m)
+                                             : "v"(tm1), "v"(v)
+                                             : "vcc");
+                            }
+                        }
+                        const u64 part = (u64)m << (a0 & 32);
+#pragma unroll
+                        for (int w = 0; w < NR; ++w)
+                            if ((a0 >> 6) == w) cm[k][w] |= part;
+                    }
+#pragma unroll
+                    for (int w = 0; w < NR; ++w) cm[k][w] = valid[k] ? (cm[k][w] | big[k][w]) : 0ull;
                 }
+                const u32 dmin = min(min(dm0, dm1), min(dm2, dm3));
+                return dmin <= tm1 ? (V)(tm1 - dmin) : (V)0;
+            } else {
+                // thresholds of 2^32 and more: whole 64-bit words
+                V below = 0;
+#pragma unroll
+                for (int k = 0; k < NR; ++k) {
+                    const int x = min(row[k], S - 1);
+#pragma unroll
+                    for (int w = 0; w < NR; ++w) cm[k][w] = 0;
+                    for (int a = 0; a < S; ++a) {
+                        const V v = Rv[(size_t)a * S + x];
+                        const bool ge = v >= t;
+                        const V u = ge ? (V)0 : v;
+                        below = u > below ? u : below;
+#pragma unroll
+                        for (int w = 0; w < NR; ++w)
+                            if ((a >> 6) == w) cm[k][w] |= (u64)ge << (a & 63);
+                    }
+                    if (!valid[k]) {
+#pragma unroll
+                        for (int w = 0; w < NR; ++w) cm[k][w] = 0;
+                    }
+                }
+                return below;
             }
-            return below;
         };
 
         // FREEC = the columns no row is matched to
@@ -155,7 +258,7 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             for (int k = 0; k < NR; ++k) FREEC[k] = ballot(valid[k] && taken[row[k]] == 0);
         };
 
-        // the residual of each row's matched cell, flag included (VMAX for rows without one)
+        // the residual of each row's matched cell (VMAX for rows without one)
         auto matched_cells = [&](V (&cell)[NR]) {
 #pragma unroll
             for (int k = 0; k < NR; ++k) {
@@ -164,27 +267,46 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             }
         };
 
-        auto augment = [&](int r0) -> bool {
-            // level 1 by hand: the lowest unmatched column among r0's own cells
-            u64 N[NR];
-            const u64 bit = 1ull << (r0 & 63);
+        // Matches rows of U in ascending order, clearing their bits, until one needs the
+        // general search: returns that row (-1: U is done).  A row whose own cells
+        // reach an unmatched column takes the lowest such column - that is what the canonical
+        // search does at its first level - in a loop that works on 32-bit halves of the masks
+        // picked at compile time; only the other rows go through the general search, which is
+        // instantiated once (match_rows; false as soon as a row cannot be matched).
+        auto greedy_rows = [&](u64 (&U)[NR]) -> int {
 #pragma unroll
-            for (int k = 0; k < NR; ++k) {
-                u64 word;
-                if constexpr (NR == 2) word = (r0 >> 6) ? cm[k][1] : cm[k][0];
-                else word = cm[k][0];
-                N[k] = ballot((word & bit) != 0) & FREEC[k];
-            }
-            if (mask_any<NR>(N)) {
-                const int d = mask_lowest<NR>(N);
+            for (int w = 0; w < NR; ++w) {
 #pragma unroll
-                for (int k = 0; k < NR; ++k) {
-                    mr[k] = row[k] == r0 ? d : mr[k];
-                    if ((d >> 6) == k) FREEC[k] &= ~(1ull << (d & 63));
+                for (int hf = 0; hf < 2; ++hf) {
+                    u32 half[NR];
+#pragma unroll
+                    for (int k = 0; k < NR; ++k) half[k] = (u32)(cm[k][w] >> (32 * hf));
+                    for (u32 z = (u32)(U[w] >> (32 * hf)); z; z &= z - 1) {
+                        const int i = __builtin_ctz(z);
+                        const int r0 = 64 * w + 32 * hf + i;
+                        const u32 bit = 1u << i;
+                        u64 N[NR];
+#pragma unroll
+                        for (int k = 0; k < NR; ++k) N[k] = ballot((half[k] & bit) != 0) & FREEC[k];
+                        U[w] &= ~((u64)bit << (32 * hf));
+                        if (!mask_any<NR>(N)) return r0;        // needs the general search
+                        const int d = mask_lowest<NR>(N);
+#pragma unroll
+                        for (int k = 0; k < NR; ++k) {
+                            mr[k] = row[k] == r0 ? d : mr[k];
+                            if ((d >> 6) == k) FREEC[k] &= ~(1ull << (d & 63));
+                        }
+                    }
                 }
-                return true;
             }
-            return bfs_augment<NR>(r0, cm, mr, FREEC, Fh, S, lane);
+            return -1;
+        };
+        auto match_rows = [&](u64 (&U)[NR]) -> bool {
+            for (;;) {
+                const int r0 = greedy_rows(U);
+                if (r0 < 0) return true;
+                if (!bfs_augment<NR>(r0, cm, mr, FREEC, Fh, S, lane)) return false;
+            }
         };
 
         // Does {R >= t} (masks already built) hold a perfect matching?  Starts from what the
@@ -194,16 +316,12 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             matched_cells(cell);
 #pragma unroll
             for (int k = 0; k < NR; ++k)
-                if ((cell[k] & (V)~VF) < t) mr[k] = -1;
+                if (cell[k] < t) mr[k] = -1;
             free_columns();
             u64 U[NR];
 #pragma unroll
             for (int k = 0; k < NR; ++k) U[k] = ballot(valid[k] && mr[k] < 0);
-#pragma unroll
-            for (int w = 0; w < NR; ++w)
-                for (u64 z = U[w]; z; z &= z - 1)
-                    if (!augment(64 * w + __builtin_ctzll(z))) return false;
-            return true;
+            return match_rows(U);
         };
 
         int32_t* srow = out_stages + (size_t)b * max_stages * S;
@@ -222,11 +340,8 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 if (feasible(t)) {
                     V cell[NR];
                     matched_cells(cell);
-                    V m = cell[0] & (V)~VF;
-                    if constexpr (NR == 2) {
-                        const V m1 = cell[1] & (V)~VF;
-                        m = m1 < m ? m1 : m;
-                    }
+                    V m = cell[0];
+                    if constexpr (NR == 2) m = cell[1] < m ? cell[1] : m;
                     lo = wave_min(m);               // >= t: the matching also lies in {R >= lo}
                     if (lo >= hi) break;
                 } else {
@@ -244,36 +359,48 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 mr[k] = -1;
                 FREEC[k] = ALLC[k];
             }
-            bool ok = true;
-            for (int r0 = 0; r0 < S && ok; ++r0) ok = augment(r0);
-            if (!ok) { status = -3; break; }
+            u64 U[NR];
+#pragma unroll
+            for (int k = 0; k < NR; ++k) U[k] = ALLC[k];
+            if (!match_rows(U)) { status = -3; break; }
 
             V cell[NR];
             matched_cells(cell);
-            V m = cell[0] & (V)~VF;
-            if constexpr (NR == 2) {
-                const V m1 = cell[1] & (V)~VF;
-                m = m1 < m ? m1 : m;
-            }
+            V m = cell[0];
+            if constexpr (NR == 2) m = cell[1] < m ? cell[1] : m;
             const V c = wave_min(m);
             if (c != tstar) { status = -3; break; }
+            u64 crossed[NR];    // rows whose cell just fell under 2^32
 #pragma unroll
             for (int k = 0; k < NR; ++k) {
+                bool cross = false;
                 if (valid[k]) {
                     const int d = mr[k];
-                    const V v = cell[k] & (V)~VF;
-                    i64 av = 0;                      // virtual bytes the embedding put in the cell
-                    if (cell[k] & VF) {
-                        const i64 l = max(PR[k], PC[d]);
-                        const i64 h = min(ER[k], EC[d]);
-                        av = (h > l ? h - l : 0) + (d == row[k] ? diag[k] : 0);
-                    }
+                    const V v = cell[k];
+                    // virtual bytes the embedding put in the cell
+                    const i64 l = max(PR[k], PC[d]);
+                    const i64 h = min(ER[k], EC[d]);
+                    const i64 av = (h > l ? h - l : 0) + (d == row[k] ? diag[k] : 0);
                     const i64 real_left = (i64)v > av ? (i64)v - av : 0;
                     const i64 real = min((i64)c, real_left);
                     srow[row[k]] = real > 0 ? d : -1;
                     brow[row[k]] = real;
-                    Rv[rowbase[k] + (u32)d] = (V)(v - c) | (cell[k] & VF);
+                    const V left = v - c;
+                    Rv[rowbase[k] + (u32)d] = left;
+                    if constexpr (WIDE) cross = (v >> 32) != 0 && (left >> 32) == 0;
                 }
+                crossed[k] = ballot(cross);
+            }
+            if constexpr (WIDE) {
+#pragma unroll
+                for (int kr = 0; kr < NR; ++kr)
+                    for (u64 z = crossed[kr]; z; z &= z - 1) {
+                        const int al = __builtin_ctzll(z);          // row 64 * kr + al
+                        const int d = (int)rdl((u32)mr[kr], al);
+#pragma unroll
+                        for (int k = 0; k < NR; ++k)
+                            if ((d >> 6) == k && lane == (d & 63)) big[k][kr] &= ~(1ull << al);
+                    }
             }
             if (lane == 0) cw[s] = (i64)c;
             ++s;

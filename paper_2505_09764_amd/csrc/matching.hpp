@@ -193,7 +193,8 @@ __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
 }
 
 // No residual exceeds L, the largest line sum: when L < 2^31 the 64-bit words of R (S*S of them,
-// flag in bit 63) are repacked in place to 32-bit words (flag in bit 31).
+// flag in bit 63) are repacked in place to 32-bit words (flag in bit 31, or dropped).
+template <bool KEEP_FLAG = true>
 __device__ __forceinline__ void repack_narrow(u64* R, int S, int lane) {
     u32* R32 = reinterpret_cast<u32*>(R);
     for (int e0 = 0; e0 < S * S; e0 += 64) {
@@ -201,7 +202,7 @@ __device__ __forceinline__ void repack_narrow(u64* R, int S, int lane) {
         u64 v = 0;
         if (e < S * S) v = R[e];
         __syncthreads();                    // chunk read before its (lower) words are rewritten
-        if (e < S * S) R32[e] = (u32)v | ((v & VFLAG) ? 0x80000000u : 0u);
+        if (e < S * S) R32[e] = (u32)v | ((KEEP_FLAG && (v & VFLAG)) ? 0x80000000u : 0u);
     }
     __syncthreads();
 }
