@@ -310,13 +310,14 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         };
 
         // Does {R >= t} (masks already built) hold a perfect matching?  Starts from what the
-        // current matching keeps in that graph; the matching it leaves lies inside the graph.
-        auto feasible = [&](V t) -> bool {
+        // current matching keeps in that graph, or from nothing (fresh: what it then leaves is
+        // the canonical matching of that graph); the matching it leaves lies inside the graph.
+        auto feasible = [&](V t, bool fresh) -> bool {
             V cell[NR];
             matched_cells(cell);
 #pragma unroll
             for (int k = 0; k < NR; ++k)
-                if (cell[k] < t) mr[k] = -1;
+                if (fresh || cell[k] < t) mr[k] = -1;
             free_columns();
             u64 U[NR];
 #pragma unroll
@@ -330,14 +331,17 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         i64 Lrem = L;
         int s = 0, status = 0;
         V hi = (V)L;            // no cell exceeds its line sum
+        V gap = 0;              // how far the last bottleneck value lay under its upper bound
         while (Lrem > 0) {
             if (s >= max_stages) { status = -2; break; }
             V lo = 0;           // largest threshold known to admit a perfect matching (0: none yet)
             V t = hi, built = 0;
+            const V hi0 = hi;
+            V down = 2 * gap;   // while nothing is known to work: step down by this, doubling
             for (;;) {
                 const V below = build(t);
                 built = t;
-                if (feasible(t)) {
+                if (feasible(t, false)) {
                     V cell[NR];
                     matched_cells(cell);
                     V m = cell[0];
@@ -348,21 +352,20 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     hi = wave_max(below);           // thresholds in (hi, t] give the graph of t again
                     if (hi <= lo) break;
                 }
-                t = lo + (hi - lo + 1) / 2;         // lo < t <= hi
+                if (lo == 0 && down != 0 && hi > down) {
+                    t = hi - down;                  // consecutive bottleneck values lie close together
+                    down *= 2;
+                } else {
+                    t = lo + (hi - lo + 1) / 2;     // lo < t <= hi
+                }
             }
             if (lo == 0) { status = -3; break; }    // not even the support holds a perfect matching
             const V tstar = lo;
+            if (hi0 > tstar) gap = hi0 - tstar;
 
+            // the stage's matching: from nothing, whatever the probes left behind
             if (built != tstar) (void)build(tstar);
-#pragma unroll
-            for (int k = 0; k < NR; ++k) {
-                mr[k] = -1;
-                FREEC[k] = ALLC[k];
-            }
-            u64 U[NR];
-#pragma unroll
-            for (int k = 0; k < NR; ++k) U[k] = ALLC[k];
-            if (!match_rows(U)) { status = -3; break; }
+            if (!feasible(tstar, true)) { status = -3; break; }
 
             V cell[NR];
             matched_cells(cell);
