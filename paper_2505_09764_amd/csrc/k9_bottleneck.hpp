@@ -301,10 +301,85 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             }
             return -1;
         };
+        // Paths of two and three hops in straight-line code: r0 -> (column d1 of r0, matched to
+        // row a1) -> [(column d2 of a1, matched to row a2) ->] unmatched column d.  They are
+        // what the general search finds at its second and third level (lowest unmatched column
+        // reached, lowest frontier row as the parent of each column on the way back) and cover
+        // nine searches in ten.  False: go deeper.
+        auto short_paths = [&](int r0) -> bool {
+            auto row_of = [&](int a) -> int {           // mr of a wave-uniform row
+                if constexpr (NR == 2) return (a >> 6) ? (int)rdl((u32)mr[1], a & 63) : (int)rdl((u32)mr[0], a & 63);
+                else return (int)rdl((u32)mr[0], a);
+            };
+            auto matched_into = [&](const u64 (&N)[NR], u64 (&F)[NR]) {
+#pragma unroll
+                for (int k = 0; k < NR; ++k) {
+                    const int m = mr[k];
+                    u64 word;
+                    if constexpr (NR == 2) word = m < 64 ? N[0] : N[1];
+                    else word = N[0];
+                    F[k] = ballot(m >= 0 && ((word >> (m & 63)) & 1));
+                }
+            };
+            auto reached = [&](const u64 (&F)[NR], u64 (&N)[NR]) {
+#pragma unroll
+                for (int k = 0; k < NR; ++k) {
+                    u64 cand = 0;
+#pragma unroll
+                    for (int w = 0; w < NR; ++w) cand |= cm[k][w] & F[w];
+                    N[k] = ballot(cand != 0);
+                }
+            };
+            auto parent_in = [&](int d, const u64 (&F)[NR]) -> int {
+                u64 par[NR];
+                column_mask<NR>(cm, d, par);
+#pragma unroll
+                for (int w = 0; w < NR; ++w) par[w] &= F[w];
+                return mask_lowest<NR>(par);
+            };
+            u64 F1[NR], N1[NR], F2[NR], N2[NR], fr[NR];
+#pragma unroll
+            for (int w = 0; w < NR; ++w) F1[w] = (r0 >> 6) == w ? 1ull << (r0 & 63) : 0ull;
+            reached(F1, N1);                            // r0's columns, all matched
+            matched_into(N1, F2);
+            reached(F2, N2);
+#pragma unroll
+            for (int k = 0; k < NR; ++k) fr[k] = N2[k] & FREEC[k];
+            int d, a1, a2 = -1, d2 = -1;
+            if (mask_any<NR>(fr)) {
+                d = mask_lowest<NR>(fr);
+                a1 = parent_in(d, F2);
+            } else {
+                u64 F3[NR], N3[NR];
+#pragma unroll
+                for (int k = 0; k < NR; ++k) N2[k] &= ~N1[k];       // newly reached, all matched
+                matched_into(N2, F3);
+                reached(F3, N3);
+#pragma unroll
+                for (int k = 0; k < NR; ++k) fr[k] = N3[k] & FREEC[k];
+                if (!mask_any<NR>(fr)) return false;
+                d = mask_lowest<NR>(fr);
+                a2 = parent_in(d, F3);
+                d2 = row_of(a2);
+                a1 = parent_in(d2, F2);
+            }
+            const int d1 = row_of(a1);
+#pragma unroll
+            for (int k = 0; k < NR; ++k) {
+                int m = mr[k];
+                m = row[k] == r0 ? d1 : m;
+                m = row[k] == a1 ? (a2 < 0 ? d : d2) : m;
+                m = row[k] == a2 ? d : m;
+                mr[k] = m;
+                if ((d >> 6) == k) FREEC[k] &= ~(1ull << (d & 63));
+            }
+            return true;
+        };
         auto match_rows = [&](u64 (&U)[NR]) -> bool {
             for (;;) {
                 const int r0 = greedy_rows(U);
                 if (r0 < 0) return true;
+                if (short_paths(r0)) continue;
                 if (!bfs_augment<NR>(r0, cm, mr, FREEC, Fh, S, lane)) return false;
             }
         };
