@@ -65,16 +65,14 @@ __device__ __forceinline__ i64 dpp_i64(i64 x) {
 }
 
 template <int G, bool VEC>
-__global__ void __launch_bounds__(K1_THREADS)
-k1_rebalance(const i64* __restrict__ traffic, i64* __restrict__ X, i64* __restrict__ wsT,
-             i64* __restrict__ wsQ, i64* __restrict__ wsPart, int S) {
-    extern __shared__ __align__(16) unsigned char k1_smem[];
+__device__ __forceinline__ void
+k1_block(const i64* __restrict__ traffic, i64* __restrict__ X, i64* __restrict__ wsT,
+         i64* __restrict__ wsQ, i64* __restrict__ wsPart, int S, int a, int b,
+         unsigned char* k1_smem) {
     constexpr int EPL = VEC ? 2 : 1;         // elements per lane
     constexpr int LPR = G / EPL;             // lanes per tile row
     constexpr bool POW2 = (LPR & (LPR - 1)) == 0;
     constexpr int MAXIT = (K1_MAX_S * LPR + K1_THREADS - 1) / K1_THREADS;
-    const int a = blockIdx.x;
-    const int b = blockIdx.y;
     const int N = S * G;
     const int P = S * G;                     // tile rows of the block, index p = d*G + i
     const int rowl = S * LPR;                // lanes per GPU row
@@ -251,6 +249,15 @@ k1_rebalance(const i64* __restrict__ traffic, i64* __restrict__ X, i64* __restri
             }
         }
     }
+}
+
+// One workgroup per (source server blockIdx.x, matrix blockIdx.y).
+template <int G, bool VEC>
+__global__ void __launch_bounds__(K1_THREADS)
+k1_rebalance(const i64* __restrict__ traffic, i64* __restrict__ X, i64* __restrict__ wsT,
+             i64* __restrict__ wsQ, i64* __restrict__ wsPart, int S) {
+    extern __shared__ __align__(16) unsigned char k1_smem[];
+    k1_block<G, VEC>(traffic, X, wsT, wsQ, wsPart, S, (int)blockIdx.x, (int)blockIdx.y, k1_smem);
 }
 
 }  // namespace fastk

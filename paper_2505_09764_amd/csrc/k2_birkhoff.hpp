@@ -71,17 +71,15 @@ inline size_t k2_lds_bytes(int S) { return k2_lds_data_bytes(S) + (size_t)(2 * 6
 // NR: rows and columns per lane; FULL: S == 64 * NR, every lane slot holds a real row (the
 // stage rows are then stored without a per-lane bounds predicate).
 template <int NR, bool FULL>
-__global__ void __launch_bounds__(K2_THREADS)
-k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
-            int32_t* __restrict__ out_stages, i64* __restrict__ out_bytes,
-            int32_t* __restrict__ out_num, i64* __restrict__ wsC, int S, int max_stages) {
-    extern __shared__ __align__(16) unsigned char k2_smem[];
+__device__ __forceinline__ void
+k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
+          int32_t* __restrict__ out_stages, i64* __restrict__ out_bytes,
+          int32_t* __restrict__ out_num, i64* __restrict__ wsC, int S, int max_stages,
+          int b, int lane, unsigned char* k2_smem) {
     u64* R = reinterpret_cast<u64*>(k2_smem);
     i64* PC = reinterpret_cast<i64*>(R + (size_t)S * S);
     i64* EC = PC + S;
     u64* Fh = reinterpret_cast<u64*>(EC + S);       // [level][2]
-    const int b = blockIdx.x;
-    const int lane = threadIdx.x;
 
     i64 diag[NR], PR[NR], ER[NR];
     const i64 L = embed_into_lds<NR>(wsQ, wsPart, b, S, lane, R, PC, EC, diag, PR, ER);
@@ -428,6 +426,17 @@ k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     };
     if (narrow) run((u32)0);
     else run((u64)0);
+}
+
+// One wavefront per matrix: matrix blockIdx.x.
+template <int NR, bool FULL>
+__global__ void __launch_bounds__(K2_THREADS)
+k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
+            int32_t* __restrict__ out_stages, i64* __restrict__ out_bytes,
+            int32_t* __restrict__ out_num, i64* __restrict__ wsC, int S, int max_stages) {
+    extern __shared__ __align__(16) unsigned char k2_smem[];
+    k2_matrix<NR, FULL>(wsQ, wsPart, out_stages, out_bytes, out_num, wsC, S, max_stages,
+                        (int)blockIdx.x, (int)threadIdx.x, k2_smem);
 }
 
 }  // namespace fastk

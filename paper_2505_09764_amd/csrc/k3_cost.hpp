@@ -45,13 +45,12 @@ __device__ __forceinline__ i64 block_reduce(i64 v, bool is_max, i64* scratch) {
 
 // sort_n: 0, or the power of two >= K capacity for which dynamic LDS was provided
 // (only when the exposed-redistribution term is needed).
-__global__ void __launch_bounds__(K3_THREADS)
-k3_cost(const i64* __restrict__ wsT, const i64* __restrict__ wsPart, const i64* __restrict__ wsC,
-        const int32_t* __restrict__ out_num, double* __restrict__ out_time, int S, int G,
-        int max_stages, double bw_up, double bw_out, double delay, int sort_n) {
-    extern __shared__ __align__(16) unsigned char k3_smem[];
+__device__ __forceinline__ void
+k3_matrix(const i64* __restrict__ wsT, const i64* __restrict__ wsPart, const i64* __restrict__ wsC,
+          const int32_t* __restrict__ out_num, double* __restrict__ out_time, int S, int G,
+          int max_stages, double bw_up, double bw_out, double delay, int sort_n, int b,
+          unsigned char* k3_smem) {
     __shared__ i64 scratch[K3_THREADS / 64];
-    const int b = blockIdx.x;
     const int tid = threadIdx.x;
     const int K = out_num[b];
     double* out = out_time + (size_t)b * 4;
@@ -127,6 +126,16 @@ k3_cost(const i64* __restrict__ wsT, const i64* __restrict__ wsPart, const i64* 
         out[2] = t2;
         out[3] = (double)big / ((double)G * bw_out);
     }
+}
+
+// One workgroup per matrix: matrix blockIdx.x.
+__global__ void __launch_bounds__(K3_THREADS)
+k3_cost(const i64* __restrict__ wsT, const i64* __restrict__ wsPart, const i64* __restrict__ wsC,
+        const int32_t* __restrict__ out_num, double* __restrict__ out_time, int S, int G,
+        int max_stages, double bw_up, double bw_out, double delay, int sort_n) {
+    extern __shared__ __align__(16) unsigned char k3_smem[];
+    k3_matrix(wsT, wsPart, wsC, out_num, out_time, S, G, max_stages, bw_up, bw_out, delay, sort_n,
+              (int)blockIdx.x, k3_smem);
 }
 
 }  // namespace fastk

@@ -82,7 +82,7 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         repack_narrow<false>(R, S, lane);
     } else {
         for (int e = lane; e < S * S; e += 64) R[e] &= ~VFLAG;
-        __syncthreads();
+        wave_sync();
     }
 
     auto run = [&](auto tag) {
@@ -245,15 +245,15 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 
         // FREEC = the columns no row is matched to
         auto free_columns = [&]() {
-            __syncthreads();
+            wave_sync();
 #pragma unroll
             for (int k = 0; k < NR; ++k)
                 if (valid[k]) taken[row[k]] = 0;
-            __syncthreads();
+            wave_sync();
 #pragma unroll
             for (int k = 0; k < NR; ++k)
                 if (mr[k] >= 0) taken[mr[k]] = 1;
-            __syncthreads();
+            wave_sync();
 #pragma unroll
             for (int k = 0; k < NR; ++k) FREEC[k] = ballot(valid[k] && taken[row[k]] == 0);
         };

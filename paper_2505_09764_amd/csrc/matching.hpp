@@ -15,6 +15,14 @@ typedef unsigned int u32;
 
 constexpr u64 VFLAG = 1ull << 63;      // LDS word flag: the cell holds virtual bytes
 
+// Orders the LDS and global accesses of the one wavefront that owns a matrix (its lanes
+// exchange data through memory).  Not a workgroup barrier: the decomposition code also runs as
+// one wavefront of a larger workgroup, where the other wavefronts must not be waited for.
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+}
+
 __device__ __forceinline__ u64 ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 __device__ __forceinline__ u32 rdl(u32 v, int lane) { return (u32)__builtin_amdgcn_readlane(v, lane); }
 __device__ __forceinline__ u64 rdl64(u64 v, int lane) {
@@ -121,7 +129,7 @@ __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
     }
     const i64* Qg = wsQ + (size_t)b * S * S;
     for (int e = lane; e < S * S; e += 64) R[e] = (u64)Qg[e];
-    __syncthreads();
+    wave_sync();
 
     i64 rsum[NR], csum[NR];
 #pragma unroll
@@ -171,7 +179,7 @@ __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
             base_c += __shfl(ic, 63, 64);
         }
     }
-    __syncthreads();
+    wave_sync();
 #pragma unroll
     for (int k = 0; k < NR; ++k) {
         const int x = lane + 64 * k;
@@ -188,7 +196,7 @@ __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
             }
         }
     }
-    __syncthreads();
+    wave_sync();
     return L;
 }
 
@@ -201,10 +209,10 @@ __device__ __forceinline__ void repack_narrow(u64* R, int S, int lane) {
         const int e = e0 + lane;
         u64 v = 0;
         if (e < S * S) v = R[e];
-        __syncthreads();                    // chunk read before its (lower) words are rewritten
+        wave_sync();                    // chunk read before its (lower) words are rewritten
         if (e < S * S) R32[e] = (u32)v | ((KEEP_FLAG && (v & VFLAG)) ? 0x80000000u : 0u);
     }
-    __syncthreads();
+    wave_sync();
 }
 
 // Canonical augmenting search from the unmatched row r0 (wave-uniform) on the graph given by
