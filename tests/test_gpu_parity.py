@@ -163,6 +163,30 @@ def test_random_shapes(oracle, torch_cuda, S, G):
     compare_batch(oracle, S, G, 400e9, 50e9, tr, res)
 
 
+@pytest.mark.parametrize("S,G", [(1, 2), (2, 8), (3, 6), (4, 8), (8, 8), (12, 8), (16, 8), (16, 4), (5, 2)])
+def test_small_clusters_alone_and_in_a_large_batch(oracle, torch_cuda, S, G):
+    """Small clusters (the sizes the paper quotes its own scheduler on): one matrix, three
+    matrices, and the same three repeated in a batch of more than 512 / S - against the oracle
+    and against each other; with a slow scale-up fabric too (the cost kernel then sorts)."""
+    rng = np.random.default_rng(900 + 10 * S + G)
+    kinds = ["uniform", "heavy", "sparse", "big"]
+    few = np.stack([_rand(rng, S, G, kinds[b % 4]) for b in range(3)])
+    reps = 512 // (3 * S) + 1
+    many = np.concatenate([few] * reps)
+    for bw_up in (400e9, 20e9):
+        say(f"[parity] small cluster S={S} G={G} bw_up={bw_up:g}")
+        one = run_gpu(torch_cuda, S, G, bw_up, 50e9, few[:1])
+        a = run_gpu(torch_cuda, S, G, bw_up, 50e9, few)
+        c = run_gpu(torch_cuda, S, G, bw_up, 50e9, many)
+        compare_batch(oracle, S, G, bw_up, 50e9, few, a)
+        for b in range(3):
+            for key in ("X", "stages", "bytes", "K", "time"):
+                assert np.array_equal(a[key][b], c[key][b]), f"{key} of matrix {b} depends on the batch around it"
+                assert np.array_equal(a[key][b], c[key][len(many) - 3 + b])
+        for key in ("X", "stages", "bytes", "K", "time"):
+            assert np.array_equal(one[key][0], a[key][0])
+
+
 def test_degenerate_inputs(oracle, torch_cuda):
     S, G = 6, 4
     N = S * G
