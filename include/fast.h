@@ -289,7 +289,10 @@ int fast_pipeline_time_batched(fast_plan_t *plan, int B, const int32_t *num_stag
  * fast_plan_timed_calls returns how many calls have been recorded (-1 if plan is NULL).
  * fast_plan_kernel_ms waits for recorded call `call` (0-based) to finish and writes its
  * three kernel durations in milliseconds to host array out_ms[3]; FAST_ERR_INVALID_ARG
- * if there is no such recorded call.
+ * if there is no such recorded call.  Up to 32 servers, with a scale-up bandwidth of at
+ * least (G-1) times the scale-out bandwidth and the default matching rule, the cost model
+ * is evaluated by the decomposition kernel itself (one launch less): its time is then part
+ * of out_ms[1] and out_ms[2] is the few microseconds between two event records.
  */
 #define FAST_MAX_TIMED_CALLS 256
 int fast_plan_set_timing(fast_plan_t *plan, int enable);

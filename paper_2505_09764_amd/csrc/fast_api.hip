@@ -146,14 +146,18 @@ void launch_k1(const fast_plan* p, int B, const i64* traffic, i64* X, hipStream_
 
 // The decomposition kernel for S servers: one or two rows per lane, and the variant without
 // bounds predicates when S fills the wavefront exactly.
-typedef void (*k2_fn)(const i64*, const i64*, int32_t*, i64*, int32_t*, i64*, int, int);
-k2_fn k2_kernel(int S) {
-    if (S == 128) return &fastk::k2_birkhoff<2, true>;
-    if (S > 64) return &fastk::k2_birkhoff<2, false>;
-    if (S == 64) return &fastk::k2_birkhoff<1, true>;
-    return &fastk::k2_birkhoff<1, false>;
+typedef void (*k2_fn)(const i64*, const i64*, int32_t*, i64*, int32_t*, i64*, int, int, const i64*,
+                      double*, int, double, double, double);
+typedef void (*k9_fn)(const i64*, const i64*, int32_t*, i64*, int32_t*, i64*, int, int);
+constexpr int K2_COST_MAX_S = 32;       // up to here the decomposition kernel can carry the cost model
+k2_fn k2_kernel(int S, bool with_cost) {
+    if (S == 128) return &fastk::k2_birkhoff<2, true, false>;
+    if (S > 64) return &fastk::k2_birkhoff<2, false, false>;
+    if (S == 64) return &fastk::k2_birkhoff<1, true, false>;
+    if (with_cost && S <= K2_COST_MAX_S) return &fastk::k2_birkhoff<1, false, true>;
+    return &fastk::k2_birkhoff<1, false, false>;
 }
-k2_fn k9_kernel(int S) {
+k9_fn k9_kernel(int S) {
     return S > 64 ? &fastk::k9_bottleneck<2> : &fastk::k9_bottleneck<1>;
 }
 
@@ -226,7 +230,7 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     const int lds2 = (int)fastk::k2_lds_bytes(S);
     hipError_t e = hipSuccess;
     if (lds2 > 48 * 1024)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2_kernel(S)),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2_kernel(S, false)),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds2);
     if (e == hipSuccess && fastk::k9_lds_bytes(S) > 48 * 1024)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(k9_kernel(S)),
@@ -295,22 +299,30 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
     if (ev) (void)hipEventRecord(ev[1], stream);
 
     i64* sb = reinterpret_cast<i64*>(out_stage_bytes);
+    const bool slow_up = p->bw_up < (double)(p->G - 1) * p->bw_out;
+    const int sort_n = slow_up ? next_pow2(p->max_stages) : 0;
+    // Small clusters are bound by the launches: there the cost model rides on the decomposition
+    // kernel's wavefront (about 3 us less per call), unless it has to sort the stage weights
+    // (slow scale-up fabric) or the fewer-stages kernel is in use.  On large clusters one
+    // wavefront takes longer over the model's reductions than kernel 3's launch costs.
+    const bool with_cost =
+        p->matching == FAST_MATCHING_SUPPORT && sort_n == 0 && p->S <= K2_COST_MAX_S;
     if (p->matching == FAST_MATCHING_BOTTLENECK)
         hipLaunchKernelGGL(k9_kernel(p->S), dim3(B), dim3(fastk::K9_THREADS),
                            fastk::k9_lds_bytes(p->S), stream, p->wsQ, p->wsPart, out_stages, sb,
                            out_num_stages, p->wsC, p->S, p->max_stages);
     else
-        hipLaunchKernelGGL(k2_kernel(p->S), dim3(B), dim3(fastk::K2_THREADS),
+        hipLaunchKernelGGL(k2_kernel(p->S, with_cost), dim3(B), dim3(fastk::K2_THREADS),
                            fastk::k2_lds_bytes(p->S), stream, p->wsQ, p->wsPart, out_stages, sb,
-                           out_num_stages, p->wsC, p->S, p->max_stages);
+                           out_num_stages, p->wsC, p->S, p->max_stages, p->wsT, out_predicted_time,
+                           p->G, p->bw_up, p->bw_out, p->delay);
     if (ev) (void)hipEventRecord(ev[2], stream);
 
-    const bool slow_up = p->bw_up < (double)(p->G - 1) * p->bw_out;
-    const int sort_n = slow_up ? next_pow2(p->max_stages) : 0;
-    hipLaunchKernelGGL(fastk::k3_cost, dim3(B), dim3(fastk::K3_THREADS),
-                       (size_t)sort_n * sizeof(i64), stream, p->wsT, p->wsPart, p->wsC,
-                       out_num_stages, out_predicted_time, p->S, p->G, p->max_stages, p->bw_up,
-                       p->bw_out, p->delay, sort_n);
+    if (!with_cost)
+        hipLaunchKernelGGL(fastk::k3_cost, dim3(B), dim3(fastk::K3_THREADS),
+                           (size_t)sort_n * sizeof(i64), stream, p->wsT, p->wsPart, p->wsC,
+                           out_num_stages, out_predicted_time, p->S, p->G, p->max_stages, p->bw_up,
+                           p->bw_out, p->delay, sort_n);
     if (ev) {
         (void)hipEventRecord(ev[3], stream);
         ++p->n_timed;

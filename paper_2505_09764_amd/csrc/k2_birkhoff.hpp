@@ -53,6 +53,7 @@
 #include <limits>
 #include <type_traits>
 
+#include "k3_cost.hpp"
 #include "matching.hpp"
 
 namespace fastk {
@@ -428,15 +429,26 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     else run((u64)0);
 }
 
-// One wavefront per matrix: matrix blockIdx.x.
-template <int NR, bool FULL>
+// One wavefront per matrix: matrix blockIdx.x.  COST: the same wavefront goes on to evaluate the
+// completion-time model of its matrix (kernel 3's body: a few reductions over what this kernel
+// and kernel 1 left in memory), which saves a launch where launches are what a call costs;
+// not available when that model needs the stage weights sorted.  A compile-time switch, so that
+// the large-cluster instantiations are exactly the stage loop and nothing else.
+template <int NR, bool FULL, bool COST>
 __global__ void __launch_bounds__(K2_THREADS)
 k2_birkhoff(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             int32_t* __restrict__ out_stages, i64* __restrict__ out_bytes,
-            int32_t* __restrict__ out_num, i64* __restrict__ wsC, int S, int max_stages) {
+            int32_t* __restrict__ out_num, i64* __restrict__ wsC, int S, int max_stages,
+            const i64* __restrict__ wsT, double* __restrict__ out_time, int G, double bw_up,
+            double bw_out, double delay) {
     extern __shared__ __align__(16) unsigned char k2_smem[];
     k2_matrix<NR, FULL>(wsQ, wsPart, out_stages, out_bytes, out_num, wsC, S, max_stages,
                         (int)blockIdx.x, (int)threadIdx.x, k2_smem);
+    if constexpr (COST) {
+        wave_sync();        // the stage count and the stage weights were stored by this wavefront
+        k3_matrix<K2_THREADS>(wsT, wsPart, wsC, out_num, out_time, S, G, max_stages, bw_up, bw_out,
+                              delay, 0, (int)blockIdx.x, (int)threadIdx.x, nullptr);
+    }
 }
 
 }  // namespace fastk

@@ -28,30 +28,34 @@ namespace fastk {
 
 constexpr int K3_THREADS = 256;
 
+template <int THREADS>
 __device__ __forceinline__ i64 block_reduce(i64 v, bool is_max, i64* scratch) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
         const i64 o = __shfl_xor(v, off, 64);
         v = is_max ? (o > v ? o : v) : v + o;
     }
+    if constexpr (THREADS == 64) return v;       // one wavefront: every lane holds the result
     const int w = threadIdx.x >> 6;
     __syncthreads();
     if ((threadIdx.x & 63) == 0) scratch[w] = v;
     __syncthreads();
     i64 r = scratch[0];
-    for (int k = 1; k < K3_THREADS / 64; ++k) r = is_max ? max(r, scratch[k]) : r + scratch[k];
+    for (int k = 1; k < THREADS / 64; ++k) r = is_max ? max(r, scratch[k]) : r + scratch[k];
     return r;
 }
 
 // sort_n: 0, or the power of two >= K capacity for which dynamic LDS was provided
 // (only when the exposed-redistribution term is needed).
+// THREADS = K3_THREADS: a workgroup of its own (tid = threadIdx.x); THREADS = 64: the tail of
+// the decomposition kernel's wavefront (tid = lane; sort_n must be 0: no barrier is reached).
+template <int THREADS>
 __device__ __forceinline__ void
 k3_matrix(const i64* __restrict__ wsT, const i64* __restrict__ wsPart, const i64* __restrict__ wsC,
           const int32_t* __restrict__ out_num, double* __restrict__ out_time, int S, int G,
           int max_stages, double bw_up, double bw_out, double delay, int sort_n, int b,
-          unsigned char* k3_smem) {
+          int tid, unsigned char* k3_smem) {
     __shared__ i64 scratch[K3_THREADS / 64];
-    const int tid = threadIdx.x;
     const int K = out_num[b];
     double* out = out_time + (size_t)b * 4;
     if (K < 0) {
@@ -59,36 +63,59 @@ k3_matrix(const i64* __restrict__ wsT, const i64* __restrict__ wsPart, const i64
         return;
     }
     i64 bal = 0, intra = 0, rowmax = 0, colmax = 0;
-    for (int a = tid; a < S; a += K3_THREADS) {
+    for (int a = tid; a < S; a += THREADS) {
         const i64* part = wsPart + ((size_t)b * S + a) * K1_PART;
         bal = max(bal, part[0]);
         intra = max(intra, part[1]);
         rowmax = max(rowmax, part[3]);
+        // column sum of T, eight loads in flight
+        const i64* col = wsT + (size_t)b * S * S + a;
         i64 cs = 0;
-        for (int r = 0; r < S; ++r) cs += wsT[((size_t)b * S + r) * S + a];
+        int r = 0;
+        for (; r + 8 <= S; r += 8) {
+            i64 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = col[(size_t)(r + j) * S];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) cs += v[j];
+        }
+        for (; r < S; ++r) cs += col[(size_t)r * S];
         colmax = max(colmax, cs);
     }
     i64 csum = 0, cmax = 0;
     const i64* c = wsC + (size_t)b * max_stages;
-    for (int s = tid; s < K; s += K3_THREADS) {
-        const i64 v = c[s];
-        csum += v;
-        cmax = max(cmax, v);
+    {
+        int s = tid;
+        for (; s + 7 * THREADS < K; s += 8 * THREADS) {
+            i64 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = c[s + j * THREADS];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                csum += v[j];
+                cmax = max(cmax, v[j]);
+            }
+        }
+        for (; s < K; s += THREADS) {
+            const i64 v = c[s];
+            csum += v;
+            cmax = max(cmax, v);
+        }
     }
-    bal = block_reduce(bal, true, scratch);
-    intra = block_reduce(intra, true, scratch);
-    const i64 big = block_reduce(max(rowmax, colmax), true, scratch);
-    csum = block_reduce(csum, false, scratch);
-    cmax = block_reduce(cmax, true, scratch);
+    bal = block_reduce<THREADS>(bal, true, scratch);
+    intra = block_reduce<THREADS>(intra, true, scratch);
+    const i64 big = block_reduce<THREADS>(max(rowmax, colmax), true, scratch);
+    csum = block_reduce<THREADS>(csum, false, scratch);
+    cmax = block_reduce<THREADS>(cmax, true, scratch);
 
     if (sort_n > 0) {
         // bitonic sort of the stage weights in LDS, padded with the largest value
         i64* l = reinterpret_cast<i64*>(k3_smem);
-        for (int s = tid; s < sort_n; s += K3_THREADS) l[s] = s < K ? c[s] : INT64_MAX;
+        for (int s = tid; s < sort_n; s += THREADS) l[s] = s < K ? c[s] : INT64_MAX;
         __syncthreads();
         for (int k = 2; k <= sort_n; k <<= 1)
             for (int j = k >> 1; j > 0; j >>= 1) {
-                for (int t = tid; t < sort_n; t += K3_THREADS) {
+                for (int t = tid; t < sort_n; t += THREADS) {
                     const int p = t ^ j;
                     if (p > t) {
                         const i64 x = l[t], y = l[p];
@@ -134,8 +161,8 @@ k3_cost(const i64* __restrict__ wsT, const i64* __restrict__ wsPart, const i64* 
         const int32_t* __restrict__ out_num, double* __restrict__ out_time, int S, int G,
         int max_stages, double bw_up, double bw_out, double delay, int sort_n) {
     extern __shared__ __align__(16) unsigned char k3_smem[];
-    k3_matrix(wsT, wsPart, wsC, out_num, out_time, S, G, max_stages, bw_up, bw_out, delay, sort_n,
-              (int)blockIdx.x, k3_smem);
+    k3_matrix<K3_THREADS>(wsT, wsPart, wsC, out_num, out_time, S, G, max_stages, bw_up, bw_out,
+                          delay, sort_n, (int)blockIdx.x, (int)threadIdx.x, k3_smem);
 }
 
 }  // namespace fastk
