@@ -145,28 +145,54 @@ spo_finish(const u64* __restrict__ wsDiag, const i64* __restrict__ wsT,
         term[i] = t;
     }
     __syncthreads();
+    // The terms are added in stage order by one thread (the sum a sequential evaluation gives);
+    // empty stages hold 0.0, which leaves a non-negative sum unchanged, so nothing is tested.
+    auto ordered_sum = [&](int n) -> double {
+        double t = 0.0;
+        int i = 1;
+        for (; i + 8 <= n; i += 8) {
+            double v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = term[i + j];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t = t + v[j];
+        }
+        for (; i < n; ++i) t = t + term[i];
+        return t;
+    };
     double tg = 0.0;
-    if (tid == 0)
-        for (int i = 1; i < N; ++i)
-            if (term[i] != 0.0) tg = tg + term[i];
+    if (tid == 0) tg = ordered_sum(N);
     __syncthreads();
     const i64* T = wsT + (size_t)b * S * S;
     for (int i = tid; i < S; i += SPO_THREADS) {
+        // largest entry of the shifted diagonal; rounding up after the maximum gives the same
+        // value as rounding every entry up first, with one division instead of S
         i64 m = 0;
-        if (i > 0)
-            for (int a = 0; a < S; ++a) {
+        if (i > 0) {
+            int a = 0;
+            for (; a + 8 <= S; a += 8) {
+                i64 v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    int d = a + j + i;
+                    d = d >= S ? d - S : d;
+                    v[j] = T[(size_t)(a + j) * S + d];
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) m = max(m, v[j]);
+            }
+            for (; a < S; ++a) {
                 int d = a + i;
                 d = d >= S ? d - S : d;
-                const i64 q = (T[(size_t)a * S + d] + G - 1) / G;
-                m = max(m, q);
+                m = max(m, T[(size_t)a * S + d]);
             }
+            m = (m + G - 1) / G;
+        }
         term[i] = m > 0 ? delay + (double)m / bw_out : 0.0;
     }
     __syncthreads();
     if (tid == 0) {
-        double ts = 0.0;
-        for (int i = 1; i < S; ++i)
-            if (term[i] != 0.0) ts = ts + term[i];
+        const double ts = ordered_sum(S);
         out[(size_t)b * 2] = tg;
         out[(size_t)b * 2 + 1] = ts;
     }
