@@ -17,6 +17,9 @@ quoted on.  Prints ONE JSON line:
   spreadout_baseline  time of the SpreadOut comparison pass and predicted-time ratios
   pipeline_analysis   time of stage order + exact redistribution volumes + pipelined completion
                       time of the same plans, and how they compare with the serial model
+  full_chip      (largest configuration only) the same workload at B = 256, one matrix per
+                 compute unit: what the chip delivers when the batch fills it; the headline
+                 B = 64 occupies a quarter of the compute units by construction
   fewer_stages_variant  the same batch with a bottleneck assignment per stage
                       (fast_plan_set_matching): stage count and time of its decomposition kernel
 """
@@ -213,6 +216,20 @@ def main():
             "mean_T_pipeline_exact_over_t_opt": float((peh[:, 0] / tp[:, 3]).mean()),
             "exact_over_worstcase_redistribution_bytes": exact / worst if worst else None}
 
+    # The same workload with one matrix per compute unit (the decomposition kernel is one
+    # wavefront and up to 133 KiB of LDS per matrix)
+    full = None
+    if S > 64 and args.batch is None:
+        Bf = 256
+        tf = W.generate_device(w, Bf, dev)
+        synf = binding.Synthesizer(S, G, w.bw_up, w.bw_out, dev)
+        outf = synf.alloc_outputs(Bf)
+        nf = max(3, min(args.steps, 5))
+        tot_f, _, _, _ = time_steps(torch, synf, tf, outf, nf, 1, False)
+        full = {"B": Bf, "ms_per_step": tot_f / nf, "schedules_per_s": Bf * nf / (tot_f * 1e-3)}
+        synf.close()
+        del tf, outf
+
     # The same batch with the fewer-stages rule (a bottleneck assignment per stage)
     synb = binding.Synthesizer(S, G, w.bw_up, w.bw_out, dev)
     synb.set_matching("bottleneck")
@@ -270,6 +287,7 @@ def main():
         "latency_b1": lat,
         "spreadout_baseline": spo,
         "pipeline_analysis": pipe,
+        "full_chip": full,
         "fewer_stages_variant": fewer,
         "cpu_baseline": cpu,
     }
