@@ -133,7 +133,14 @@ void launch_k1(const fast_plan* p, int B, const i64* traffic, i64* X, hipStream_
     const size_t lds = fastk::k1_lds_bytes(p->S, G);
     const bool vec = (G % 2 == 0) && ((reinterpret_cast<uintptr_t>(traffic) |
                                        reinterpret_cast<uintptr_t>(X)) % 16 == 0);
-    if constexpr (G % 2 == 0) {
+    if constexpr (G == 2 || G == 4 || G == 8) {
+        if (vec) {
+            hipLaunchKernelGGL((fastk::k1_rebalance_tiles<G>), grid, block,
+                               fastk::k1_tiles_lds_bytes(G), stream, traffic, X, p->wsT, p->wsQ,
+                               p->wsPart, p->S);
+            return;
+        }
+    } else if constexpr (G % 2 == 0) {
         if (vec) {
             hipLaunchKernelGGL((fastk::k1_rebalance<G, true>), grid, block, lds, stream, traffic,
                                X, p->wsT, p->wsQ, p->wsPart, p->S);

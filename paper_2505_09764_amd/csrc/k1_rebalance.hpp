@@ -27,6 +27,10 @@
 // HBM traffic: the row block is read once (8*G*N bytes) and X written once
 // (8*G*N bytes), both with the non-temporal hint since neither is touched again
 // by this kernel; everything else lives in LDS (3 tables of S*G words).
+//
+// k1_block is the general form (any G up to 8, any alignment).  For G = 2, 4, 8 and 16-byte
+// aligned buffers k1_block_tiles below computes the same outputs without the three phases:
+// each tile is worked out in registers by the lanes that loaded it.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -249,6 +253,182 @@ k1_block(const i64* __restrict__ traffic, i64* __restrict__ X, i64* __restrict__
             }
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// The same block without the load -> barrier -> store shape (G = 2, 4, 8 with 16-byte
+// aligned buffers).  A tile's balancing depends on that tile's G row sums only, and the G/2
+// lanes that load a tile's rows (two columns each) are neighbours: after the DPP exchange
+// each of them holds all G row sums, works the tile out in registers - targets, surplus and
+// deficit intervals, its own two columns of X - and stores its part of X right away, 16 bytes
+// per lane on the addresses it loaded from.  No LDS tables, no barrier between the loads and
+// the stores: a wavefront's stores overlap the other wavefronts' loads, as in a plain copy.
+// Only the per-server records still go through LDS (the same partial-sum slots, one
+// lane per tile adds to them), and the block needs two barriers in all.
+// ---------------------------------------------------------------------------
+inline size_t k1_tiles_lds_bytes(int G) {
+    return (size_t)((2 * G + 1) * K1_SLOTS + 2 * G + 2) * sizeof(i64);
+}
+
+template <int G>
+__device__ __forceinline__ void
+k1_block_tiles(const i64* __restrict__ traffic, i64* __restrict__ X, i64* __restrict__ wsT,
+               i64* __restrict__ wsQ, i64* __restrict__ wsPart, int S, int a, int b,
+               unsigned char* k1_smem) {
+    constexpr int LPR = G / 2;               // lanes per tile row (two elements per lane)
+    static_assert(G % 2 == 0 && (LPR & (LPR - 1)) == 0 && LPR <= 4, "G = 2, 4 or 8");
+    constexpr int MAXIT = (K1_MAX_S * LPR + K1_THREADS - 1) / K1_THREADS;
+    const int N = S * G;
+    const int rowl = S * LPR;                // lanes per GPU row
+    u64* acc = reinterpret_cast<u64*>(k1_smem);            // [(2G+1)][SLOTS]
+    i64* intra_in = reinterpret_cast<i64*>(acc + (2 * G + 1) * K1_SLOTS);
+    i64* intra_out = intra_in + G;
+    i64* misc = intra_out + G;               // [0] negative flag
+    const int tid = threadIdx.x;
+    for (int t = tid; t < (2 * G + 1) * K1_SLOTS + 2 * G + 2; t += K1_THREADS) acc[t] = 0;
+    __syncthreads();
+
+    const i64* blk = traffic + ((size_t)b * N + (size_t)a * G) * N;
+    i64* xblk = X + ((size_t)b * N + (size_t)a * G) * N;
+    const int ql = tid & (LPR - 1);          // which pair of columns of the tile this lane holds
+    i64 orv = 0;
+#pragma unroll
+    for (int it = 0; it < MAXIT; ++it) {
+        const int hp = tid + it * K1_THREADS;
+        if ((hp & ~63) >= rowl) break;       // nothing left for this wavefront (wave-uniform)
+        const bool live = hp < rowl;
+        const int d = hp / LPR;
+        const bool intra = live && d == a;
+
+        // the tile's rows: two columns per lane, all loads in flight together
+        ll2 w[G];
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            w[i] = ll2{0, 0};
+            if (live) w[i] = __builtin_nontemporal_load(reinterpret_cast<const ll2*>(blk + (size_t)i * N + (size_t)hp * 2));
+        }
+        i64 r[G];
+        i64 col0 = 0, col1 = 0;
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            i64 x0 = w[i].x, x1 = w[i].y;
+            if (intra) {                     // the GPU diagonal uses no link
+                if (2 * ql == i) x0 = 0;
+                if (2 * ql + 1 == i) x1 = 0;
+                col0 += x0;
+                col1 += x1;
+            }
+            orv |= x0 | x1;
+            i64 sum = x0 + x1;
+            if constexpr (LPR >= 2) sum += dpp_i64<0xB1>(sum);    // quad_perm [1,0,3,2]
+            if constexpr (LPR >= 4) sum += dpp_i64<0x4E>(sum);    // quad_perm [2,3,0,1]
+            r[i] = sum;
+        }
+        if (intra) {
+            // intra-server tile: per-GPU bytes out (row sums) and in (column sums); nothing to balance
+            intra_in[2 * ql] = col0;
+            intra_in[2 * ql + 1] = col1;
+            if (ql == 0) {
+#pragma unroll
+                for (int i = 0; i < G; ++i) intra_out[i] = r[i];
+            }
+#pragma unroll
+            for (int i = 0; i < G; ++i) r[i] = 0;
+        }
+
+        // the tile, worked out by each of its lanes
+        i64 tot = 0;
+#pragma unroll
+        for (int i = 0; i < G; ++i) tot += r[i];
+        const i64 q = tot / G;
+        const int rho = (int)(tot - q * G);
+        // first pass over the lanes k of the tile: where each surplus / deficit starts on its
+        // line; this lane keeps the intervals of its own two columns, one lane keeps the books
+        i64 lk[2] = {0, 0}, hk[2] = {0, 0};
+        {
+            i64 ps = 0, pd = 0;
+            const bool book = live && ql == 0 && d != a;
+            const int slot = d & (K1_SLOTS - 1);
+#pragma unroll
+            for (int k = 0; k < G; ++k) {
+                const i64 tk = q + (k < rho ? 1 : 0);
+                const i64 diff = r[k] - tk;
+                const bool surplus = diff > 0;
+                const i64 sk = surplus ? diff : 0;
+                const i64 dk = sk - diff;
+                const i64 base = surplus ? ps : pd;
+                if ((k >> 1) == ql) {
+                    lk[k & 1] = base;
+                    hk[k & 1] = base + (surplus ? sk : dk);
+                }
+                ps += sk;
+                pd += dk;
+                if (book) {
+                    atomicAdd(&acc[k * K1_SLOTS + slot], (u64)sk);
+                    atomicAdd(&acc[(G + k) * K1_SLOTS + slot], (u64)dk);
+                }
+            }
+            if (book) atomicAdd(&acc[2 * G * K1_SLOTS + slot], (u64)tot);
+        }
+        if (live && ql == 0) {
+            wsT[((size_t)b * S + a) * S + d] = tot;
+            wsQ[((size_t)b * S + a) * S + d] = q + (rho > 0 ? 1 : 0);
+        }
+
+        // second pass over the rows i: row i hands off the interval [ps, ps + s_i) of the surplus
+        // line (empty for a deficit row); this lane's two columns of row i go out at once
+        if (live) {
+            i64 ps = 0;
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                const i64 ti = q + (i < rho ? 1 : 0);
+                const i64 diff = r[i] - ti;
+                const i64 si = diff > 0 ? diff : 0;
+                i64 out[2];
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const i64 l = max(ps, lk[c]);
+                    const i64 h = min(ps + si, hk[c]);
+                    const i64 wd = h - l;
+                    out[c] = wd > 0 ? wd : 0;
+                }
+                if ((i >> 1) == ql) out[i & 1] = r[i] - si;     // what the GPU keeps for its own lane
+                ps += si;
+                __builtin_nontemporal_store(ll2{out[0], out[1]},
+                                            reinterpret_cast<ll2*>(xblk + (size_t)i * N + (size_t)hp * 2));
+            }
+        }
+    }
+    if (orv < 0) misc[0] = 1;
+    __syncthreads();
+
+    if (tid >= K1_THREADS - 64) {
+        // last wave: lane j < 2G sums GPU j's hand-off (or hand-in) slots, lane 2G the tile totals
+        const int j = tid - (K1_THREADS - 64);
+        u64 s = 0;
+        if (j < 2 * G + 1) {
+#pragma unroll
+            for (int k = 0; k < K1_SLOTS; ++k) s += acc[j * K1_SLOTS + k];
+        }
+        i64 bal = j < 2 * G ? (i64)s : 0;
+        i64 intra = j < 2 * G ? intra_in[j] : 0;      // intra_in and intra_out are adjacent
+#pragma unroll
+        for (int m = 1; m < 16; m <<= 1) {
+            bal = max(bal, __shfl_xor(bal, m));
+            intra = max(intra, __shfl_xor(intra, m));
+        }
+        i64* part = wsPart + ((size_t)b * S + a) * K1_PART;
+        if (j == 0) { part[0] = bal; part[1] = intra; part[2] = misc[0]; }
+        if (j == 2 * G) part[3] = (i64)s;
+    }
+}
+
+template <int G>
+__global__ void __launch_bounds__(K1_THREADS)
+k1_rebalance_tiles(const i64* __restrict__ traffic, i64* __restrict__ X, i64* __restrict__ wsT,
+                   i64* __restrict__ wsQ, i64* __restrict__ wsPart, int S) {
+    extern __shared__ __align__(16) unsigned char k1_smem[];
+    k1_block_tiles<G>(traffic, X, wsT, wsQ, wsPart, S, (int)blockIdx.x, (int)blockIdx.y, k1_smem);
 }
 
 // One workgroup per (source server blockIdx.x, matrix blockIdx.y).
