@@ -336,68 +336,81 @@ k1_block_tiles(const i64* __restrict__ traffic, i64* __restrict__ X, i64* __rest
             for (int i = 0; i < G; ++i) r[i] = 0;
         }
 
-        // the tile, worked out by each of its lanes
-        i64 tot = 0;
+        // the tile, worked out by each of its lanes - in 32-bit arithmetic when every tile of the
+        // wavefront has non-negative row sums and a total below 2^31 (all intermediate values
+        // are then bounded by the total), in 64-bit arithmetic otherwise
+        i64 tot = 0, rneg = 0;
 #pragma unroll
-        for (int i = 0; i < G; ++i) tot += r[i];
-        const i64 q = tot / G;
-        const int rho = (int)(tot - q * G);
-        // first pass over the lanes k of the tile: where each surplus / deficit starts on its
-        // line; this lane keeps the intervals of its own two columns, one lane keeps the books
-        i64 lk[2] = {0, 0}, hk[2] = {0, 0};
-        {
-            i64 ps = 0, pd = 0;
-            const bool book = live && ql == 0 && d != a;
-            const int slot = d & (K1_SLOTS - 1);
+        for (int i = 0; i < G; ++i) {
+            tot += r[i];
+            rneg |= r[i];
+        }
+        const bool book = live && ql == 0 && d != a;       // one lane per cross-server tile keeps the books
+        const int slot = d & (K1_SLOTS - 1);
+        auto tile = [&](auto tag) {
+            typedef decltype(tag) V;
+            V rv[G];
 #pragma unroll
-            for (int k = 0; k < G; ++k) {
-                const i64 tk = q + (k < rho ? 1 : 0);
-                const i64 diff = r[k] - tk;
-                const bool surplus = diff > 0;
-                const i64 sk = surplus ? diff : 0;
-                const i64 dk = sk - diff;
-                const i64 base = surplus ? ps : pd;
-                if ((k >> 1) == ql) {
-                    lk[k & 1] = base;
-                    hk[k & 1] = base + (surplus ? sk : dk);
-                }
-                ps += sk;
-                pd += dk;
-                if (book) {
-                    atomicAdd(&acc[k * K1_SLOTS + slot], (u64)sk);
-                    atomicAdd(&acc[(G + k) * K1_SLOTS + slot], (u64)dk);
+            for (int i = 0; i < G; ++i) rv[i] = (V)r[i];
+            const V q = (V)tot / (V)G;
+            const int rho = (int)((V)tot - q * (V)G);
+            // first pass over the lanes k of the tile: where each surplus / deficit starts on its
+            // line; this lane keeps the intervals of its own two columns, one lane keeps the books
+            V lk[2] = {0, 0}, hk[2] = {0, 0};
+            {
+                V ps = 0, pd = 0;
+#pragma unroll
+                for (int k = 0; k < G; ++k) {
+                    const V tk = q + (k < rho ? 1 : 0);
+                    const V diff = rv[k] - tk;
+                    const bool surplus = diff > 0;
+                    const V sk = surplus ? diff : 0;
+                    const V dk = sk - diff;
+                    const V base = surplus ? ps : pd;
+                    if ((k >> 1) == ql) {
+                        lk[k & 1] = base;
+                        hk[k & 1] = base + (surplus ? sk : dk);
+                    }
+                    ps += sk;
+                    pd += dk;
+                    if (book) {
+                        atomicAdd(&acc[k * K1_SLOTS + slot], (u64)(i64)sk);
+                        atomicAdd(&acc[(G + k) * K1_SLOTS + slot], (u64)(i64)dk);
+                    }
                 }
             }
-            if (book) atomicAdd(&acc[2 * G * K1_SLOTS + slot], (u64)tot);
-        }
-        if (live && ql == 0) {
-            wsT[((size_t)b * S + a) * S + d] = tot;
-            wsQ[((size_t)b * S + a) * S + d] = q + (rho > 0 ? 1 : 0);
-        }
-
-        // second pass over the rows i: row i hands off the interval [ps, ps + s_i) of the surplus
-        // line (empty for a deficit row); this lane's two columns of row i go out at once
-        if (live) {
-            i64 ps = 0;
-#pragma unroll
-            for (int i = 0; i < G; ++i) {
-                const i64 ti = q + (i < rho ? 1 : 0);
-                const i64 diff = r[i] - ti;
-                const i64 si = diff > 0 ? diff : 0;
-                i64 out[2];
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const i64 l = max(ps, lk[c]);
-                    const i64 h = min(ps + si, hk[c]);
-                    const i64 wd = h - l;
-                    out[c] = wd > 0 ? wd : 0;
-                }
-                if ((i >> 1) == ql) out[i & 1] = r[i] - si;     // what the GPU keeps for its own lane
-                ps += si;
-                __builtin_nontemporal_store(ll2{out[0], out[1]},
-                                            reinterpret_cast<ll2*>(xblk + (size_t)i * N + (size_t)hp * 2));
+            if (live && ql == 0) {
+                wsT[((size_t)b * S + a) * S + d] = tot;
+                wsQ[((size_t)b * S + a) * S + d] = (i64)(q + (rho > 0 ? 1 : 0));
             }
-        }
+            // second pass over the rows i: row i hands off the interval [ps, ps + s_i) of the
+            // surplus line (empty for a deficit row); this lane's two columns of row i go out at once
+            if (live) {
+                V ps = 0;
+#pragma unroll
+                for (int i = 0; i < G; ++i) {
+                    const V ti = q + (i < rho ? 1 : 0);
+                    const V diff = rv[i] - ti;
+                    const V si = diff > 0 ? diff : 0;
+                    V out[2];
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) {
+                        const V l = max(ps, lk[c]);
+                        const V h = min((V)(ps + si), hk[c]);
+                        const V wd = h - l;
+                        out[c] = wd > 0 ? wd : 0;
+                    }
+                    if ((i >> 1) == ql) out[i & 1] = rv[i] - si;    // what the GPU keeps for its own lane
+                    ps += si;
+                    __builtin_nontemporal_store(ll2{(i64)out[0], (i64)out[1]},
+                                                reinterpret_cast<ll2*>(xblk + (size_t)i * N + (size_t)hp * 2));
+                }
+            }
+        };
+        if (book) atomicAdd(&acc[2 * G * K1_SLOTS + slot], (u64)tot);
+        const bool wide = __builtin_amdgcn_ballot_w64(rneg < 0 || tot >= ((i64)1 << 31)) != 0;
+        if (wide) tile((i64)0);
+        else tile((int)0);
     }
     if (orv < 0) misc[0] = 1;
     __syncthreads();
