@@ -187,6 +187,50 @@ def test_small_clusters_alone_and_in_a_large_batch(oracle, torch_cuda, S, G):
             assert np.array_equal(one[key][0], a[key][0])
 
 
+@pytest.mark.parametrize("S,G", [(5, 2), (9, 4), (16, 8), (33, 8), (7, 6)])
+def test_buffers_not_aligned_to_16_bytes(oracle, torch_cuda, S, G):
+    """The 16-byte-per-lane forms of the streaming kernels need 16-byte aligned traffic and
+    X buffers; with either of them 8 bytes off the general forms run instead.  Same results."""
+    torch = torch_cuda
+    from paper_2505_09764_amd.binding import Synthesizer
+    rng = np.random.default_rng(400 + 10 * S + G)
+    N = S * G
+    B = 3
+    tr = np.stack([_rand(rng, S, G, k) for k in ("uniform", "heavy", "sparse")])
+    say(f"[parity] unaligned buffers S={S} G={G}")
+    want = run_gpu(torch, S, G, 400e9, 50e9, tr)
+    dev = torch.device("cuda:0")
+    syn = Synthesizer(S, G, 400e9, 50e9, dev)
+    for shift_in, shift_out in ((1, 0), (0, 1), (1, 1)):
+        raw_in = torch.zeros(B * N * N + 2, dtype=torch.int64, device=dev)
+        base = 0 if raw_in.data_ptr() % 16 == 0 else 1          # element index of a 16-byte boundary
+        t = raw_in[base + shift_in: base + shift_in + B * N * N].view(B, N, N)
+        t.copy_(torch.from_numpy(tr))
+        out = syn.alloc_outputs(B)
+        raw_out = torch.full((B * N * N + 2,), SENT64, dtype=torch.int64, device=dev)
+        obase = 0 if raw_out.data_ptr() % 16 == 0 else 1
+        out.rebalance = raw_out[obase + shift_out: obase + shift_out + B * N * N].view(B, N, N)
+        assert t.data_ptr() % 16 == 8 * shift_in and out.rebalance.data_ptr() % 16 == 8 * shift_out
+        syn.synthesize(t, out)
+        spo = syn.spreadout(t)
+        spo_want = syn.spreadout(torch.from_numpy(tr).to(dev))
+        torch.cuda.synchronize()
+        assert np.array_equal(out.rebalance.cpu().numpy(), want["X"])
+        assert np.array_equal(out.num_stages.cpu().numpy(), want["K"])
+        assert np.array_equal(out.predicted_time.cpu().numpy(), want["time"])
+        for b in range(B):
+            K = int(want["K"][b])
+            assert np.array_equal(out.stages[b, :K].cpu().numpy(), want["stages"][b, :K])
+            assert np.array_equal(out.stage_bytes[b, :K].cpu().numpy(), want["bytes"][b, :K])
+        assert torch.equal(spo, spo_want)
+        # nothing written outside the X buffer
+        edge = raw_out.cpu().numpy()
+        lo_, hi_ = obase + shift_out, obase + shift_out + B * N * N
+        assert (edge[:lo_] == SENT64).all() and (edge[hi_:] == SENT64).all()
+    syn.close()
+    compare_batch(oracle, S, G, 400e9, 50e9, tr, want)
+
+
 def test_degenerate_inputs(oracle, torch_cuda):
     S, G = 6, 4
     N = S * G
