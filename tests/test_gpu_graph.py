@@ -23,7 +23,8 @@ def _run_all(syn, traffic, out):
     return spo, order, off, redis, pipe
 
 
-def test_graph_replays_match_eager():
+@pytest.mark.parametrize("matching", ["support", "bottleneck"])
+def test_graph_replays_match_eager(matching):
     import torch
     from paper_2505_09764_amd.binding import Synthesizer
     from paper_2505_09764_amd import workloads as W
@@ -32,9 +33,11 @@ def test_graph_replays_match_eager():
     B = 6
     inputs = [W.generate_device(W.config(3, seed=100 + k), B, dev) for k in range(3)]
     w = W.config(3)
-    say(f"[graph] {w.name} B={B}")
+    say(f"[graph] {w.name} B={B} matching={matching}")
     syn = Synthesizer(w.S, w.G, w.bw_up, w.bw_out, dev)
     ref = Synthesizer(w.S, w.G, w.bw_up, w.bw_out, dev)
+    syn.set_matching(matching)
+    ref.set_matching(matching)
     static_in = inputs[0].clone()
     out = syn.alloc_outputs(B)
 
