@@ -9,8 +9,7 @@
 #include <new>
 
 #include "k1_rebalance.hpp"
-#include "k2_birkhoff.hpp"
-#include "k9_bottleneck.hpp"
+#include "decompose.hpp"
 #include "k3_cost.hpp"
 #include "k4_spreadout.hpp"
 #include "k5_build_traffic.hpp"
@@ -151,22 +150,6 @@ void launch_k1(const fast_plan* p, int B, const i64* traffic, i64* X, hipStream_
                        p->wsT, p->wsQ, p->wsPart, p->S);
 }
 
-// The decomposition kernel for S servers: one or two rows per lane, and the variant without
-// bounds predicates when S fills the wavefront exactly.
-typedef void (*k2_fn)(const i64*, const i64*, int32_t*, i64*, int32_t*, i64*, int, int, const i64*,
-                      double*, int, double, double, double);
-typedef void (*k9_fn)(const i64*, const i64*, int32_t*, i64*, int32_t*, i64*, int, int);
-constexpr int K2_COST_MAX_S = 32;       // up to here the decomposition kernel can carry the cost model
-k2_fn k2_kernel(int S, bool with_cost) {
-    if (S == 128) return &fastk::k2_birkhoff<2, true, false>;
-    if (S > 64) return &fastk::k2_birkhoff<2, false, false>;
-    if (S == 64) return &fastk::k2_birkhoff<1, true, false>;
-    if (with_cost && S <= K2_COST_MAX_S) return &fastk::k2_birkhoff<1, false, true>;
-    return &fastk::k2_birkhoff<1, false, false>;
-}
-k9_fn k9_kernel(int S) {
-    return S > 64 ? &fastk::k9_bottleneck<2> : &fastk::k9_bottleneck<1>;
-}
 
 // The stage-walk kernel: with or without pair lists, with or without a stage order, and the
 // variant without store predicates when S is a multiple of its 64 source servers per wavefront.
@@ -232,17 +215,7 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     p->n_timed = 0;
     p->ev = nullptr;
 
-    // The decomposition kernel keeps the S x S residual in LDS: up to 130 KiB of the
-    // CU's 160 KiB, which has to be requested explicitly above 64 KiB.
-    const int lds2 = (int)fastk::k2_lds_bytes(S);
-    hipError_t e = hipSuccess;
-    if (lds2 > 48 * 1024)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2_kernel(S, false)),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds2);
-    if (e == hipSuccess && fastk::k9_lds_bytes(S) > 48 * 1024)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k9_kernel(S)),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)fastk::k9_lds_bytes(S));
+    hipError_t e = fastk::decompose_prepare(S);
     if (e == hipSuccess && link_bw_up < (double)(G - 1) * link_bw_out)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::k3_cost),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -313,16 +286,14 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
     // (slow scale-up fabric) or the fewer-stages kernel is in use.  On large clusters one
     // wavefront takes longer over the model's reductions than kernel 3's launch costs.
     const bool with_cost =
-        p->matching == FAST_MATCHING_SUPPORT && sort_n == 0 && p->S <= K2_COST_MAX_S;
+        p->matching == FAST_MATCHING_SUPPORT && sort_n == 0 && p->S <= fastk::K2_COST_MAX_S;
     if (p->matching == FAST_MATCHING_BOTTLENECK)
-        hipLaunchKernelGGL(k9_kernel(p->S), dim3(B), dim3(fastk::K9_THREADS),
-                           fastk::k9_lds_bytes(p->S), stream, p->wsQ, p->wsPart, out_stages, sb,
-                           out_num_stages, p->wsC, p->S, p->max_stages);
+        fastk::launch_k9(p->S, B, stream, p->wsQ, p->wsPart, out_stages, sb, out_num_stages, p->wsC,
+                         p->max_stages);
     else
-        hipLaunchKernelGGL(k2_kernel(p->S, with_cost), dim3(B), dim3(fastk::K2_THREADS),
-                           fastk::k2_lds_bytes(p->S), stream, p->wsQ, p->wsPart, out_stages, sb,
-                           out_num_stages, p->wsC, p->S, p->max_stages, p->wsT, out_predicted_time,
-                           p->G, p->bw_up, p->bw_out, p->delay);
+        fastk::launch_k2(p->S, with_cost, B, stream, p->wsQ, p->wsPart, out_stages, sb,
+                         out_num_stages, p->wsC, p->max_stages, p->wsT, out_predicted_time, p->G,
+                         p->bw_up, p->bw_out, p->delay);
     if (ev) (void)hipEventRecord(ev[2], stream);
 
     if (!with_cost)

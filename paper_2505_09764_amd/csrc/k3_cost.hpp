@@ -155,8 +155,9 @@ k3_matrix(const i64* __restrict__ wsT, const i64* __restrict__ wsPart, const i64
     }
 }
 
-// One workgroup per matrix: matrix blockIdx.x.
-__global__ void __launch_bounds__(K3_THREADS)
+// One workgroup per matrix: matrix blockIdx.x.  (static: the header is included by more than
+// one translation unit of the library.)
+static __global__ void __launch_bounds__(K3_THREADS)
 k3_cost(const i64* __restrict__ wsT, const i64* __restrict__ wsPart, const i64* __restrict__ wsC,
         const int32_t* __restrict__ out_num, double* __restrict__ out_time, int S, int G,
         int max_stages, double bw_up, double bw_out, double delay, int sort_n) {
