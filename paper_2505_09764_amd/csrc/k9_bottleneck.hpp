@@ -96,12 +96,8 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             else return wave_min_u64(v);
         };
         auto wave_max = [&](V v) -> V {
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const V o = __shfl_xor(v, off, 64);
-                v = o > v ? o : v;
-            }
-            return v;
+            if constexpr (sizeof(V) == 4) return wave_max_u32(v);
+            else return wave_max_u64(v);
         };
         int row[NR];
         bool valid[NR];

@@ -60,6 +60,25 @@ __device__ __forceinline__ u64 wave_min_u64(u64 x) {
     const u32 mlo = wave_min_u32(lo);
     return ((u64)mhi << 32) | mlo;
 }
+// max over the 64 lanes (all lanes must be active), result wave-uniform
+__device__ __forceinline__ u32 wave_max_u32(u32 v) {
+    asm volatile(
+        "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(v));
+    return rdl(v, 63);
+}
+__device__ __forceinline__ u64 wave_max_u64(u64 x) {
+    const u32 hi = (u32)(x >> 32);
+    const u32 mhi = wave_max_u32(hi);
+    const u32 lo = hi == mhi ? (u32)x : 0u;
+    return ((u64)mhi << 32) | wave_max_u32(lo);
+}
 // v[lane] = val for one lane; val and lane are wave-uniform
 __device__ __forceinline__ void wrlane(u32& v, u32 val, int lane) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0"
