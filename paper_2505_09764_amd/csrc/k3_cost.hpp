@@ -23,17 +23,20 @@
 #include <stdint.h>
 
 #include "k1_rebalance.hpp"
+#include "matching.hpp"
 
 namespace fastk {
 
 constexpr int K3_THREADS = 256;
 
+// Sum or maximum (of non-negative values) over the workgroup, the same in every thread.
 template <int THREADS>
 __device__ __forceinline__ i64 block_reduce(i64 v, bool is_max, i64* scratch) {
+    if (is_max) {
+        v = (i64)wave_max_u64((u64)v);           // DPP, result wave-uniform
+    } else {
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const i64 o = __shfl_xor(v, off, 64);
-        v = is_max ? (o > v ? o : v) : v + o;
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
     }
     if constexpr (THREADS == 64) return v;       // one wavefront: every lane holds the result
     const int w = threadIdx.x >> 6;
