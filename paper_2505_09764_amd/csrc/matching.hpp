@@ -50,11 +50,10 @@ __device__ __forceinline__ u32 wave_min_u32(u32 v) {
 }
 __device__ __forceinline__ u64 wave_min_u64(u64 x) {
     const u32 hi = (u32)(x >> 32);
-    const u64 small = ballot(hi == 0);
-    if (small) {      // some value fits 32 bits: the minimum is among those
-        const u32 lo = hi == 0 ? (u32)x : 0xFFFFFFFFu;
-        return wave_min_u32(lo);
-    }
+    // if some value fits 32 bits the minimum is among those: try that first, without a test
+    // in front of the reduction (all-ones: none fits, or the minimum really is 2^32 - 1)
+    const u32 first = wave_min_u32(hi == 0 ? (u32)x : 0xFFFFFFFFu);
+    if (__builtin_expect(first != 0xFFFFFFFFu, 1)) return first;
     const u32 mhi = wave_min_u32(hi);
     const u32 lo = hi == mhi ? (u32)x : 0xFFFFFFFFu;
     const u32 mlo = wave_min_u32(lo);
