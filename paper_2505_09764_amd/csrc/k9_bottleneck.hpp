@@ -132,7 +132,11 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         // lane + 64k).  Returns, per lane, an upper bound on the cell values below t seen in its
         // columns that is itself below t (the largest such value, unless a low half of a large
         // cell comes in), 0 if there is none.
-        auto build = [&](V t) -> V {
+        // sfix: 64 * NR when S is exactly that (row strides and loop bounds are then compile-time
+        // constants: the loads take immediate offsets and pair up), 0 for any other S
+        auto build_s = [&](V t, auto sfix) -> V {
+            constexpr int SF = decltype(sfix)::value;
+            const int SS = SF ? SF : S;
             if (!WIDE || t <= (V)0xFFFFFFFFu) {
                 // 32-bit words (the low halves in 64-bit mode: stride 2)
                 constexpr int ST = WIDE ? 2 : 1;
@@ -141,13 +145,13 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 u32 dm0 = 0xFFFFFFFFu, dm1 = 0xFFFFFFFFu, dm2 = 0xFFFFFFFFu, dm3 = 0xFFFFFFFFu;
 #pragma unroll
                 for (int k = 0; k < NR; ++k) {
-                    const int x = min(row[k], S - 1);       // lanes past S re-read the last column
+                    const int x = min(row[k], SS - 1);       // lanes past SS re-read the last column
 #pragma unroll
                     for (int w = 0; w < NR; ++w) cm[k][w] = 0;
-                    for (int a0 = 0; a0 < S; a0 += 32) {
-                        const u32* col = R32 + ((size_t)a0 * S + x) * ST;
+                    for (int a0 = 0; a0 < SS; a0 += 32) {
+                        const u32* col = R32 + ((size_t)a0 * SS + x) * ST;
                         u32 m;
-                        if (a0 + 32 <= S) {
+                        if (a0 + 32 <= SS) {
                             // Four groups of eight rows, each with its own mask and minimum, so
                             // that no instruction waits for the one before it; rows in descending
                             // order, every step shifting its group's mask left by one.  The borrow
@@ -183,7 +187,7 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                                     for (int g = 0; g < 4; ++g)
-                                        w16[j][g] = col[(size_t)(8 * g + h + j) * S * ST];
+                                        w16[j][g] = col[(size_t)(8 * g + h + j) * SS * ST];
 #pragma unroll
                                 for (int j = 3; j >= 0; --j)
                                     step4(w16[j][0], w16[j][1], w16[j][2], w16[j][3]);
@@ -191,8 +195,8 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                             m = m0 | (m1 << 8) | (m2 << 16) | (m3 << 24);
                         } else {
                             m = 0;
-                            for (int i = S - a0 - 1; i >= 0; --i) {
-                                const u32 v = col[(size_t)i * S * ST];
+                            for (int i = SS - a0 - 1; i >= 0; --i) {
+                                const u32 v = col[(size_t)i * SS * ST];
                                 u32 d;
                                 asm volatile("v_sub_co_u32_e32 %0, vcc, %3, %4\n\t"
                                              "v_min_u32_e32 %1, %0, %1\n\t"
@@ -218,11 +222,11 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 V below = 0;
 #pragma unroll
                 for (int k = 0; k < NR; ++k) {
-                    const int x = min(row[k], S - 1);
+                    const int x = min(row[k], SS - 1);
 #pragma unroll
                     for (int w = 0; w < NR; ++w) cm[k][w] = 0;
-                    for (int a = 0; a < S; ++a) {
-                        const V v = Rv[(size_t)a * S + x];
+                    for (int a = 0; a < SS; ++a) {
+                        const V v = Rv[(size_t)a * SS + x];
                         const bool ge = v >= t;
                         const V u = ge ? (V)0 : v;
                         below = u > below ? u : below;
@@ -237,6 +241,10 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 }
                 return below;
             }
+        };
+        auto build = [&](V t) -> V {
+            if (S == 64 * NR) return build_s(t, std::integral_constant<int, 64 * NR>{});
+            return build_s(t, std::integral_constant<int, 0>{});
         };
 
         // FREEC = the columns no row is matched to
