@@ -75,8 +75,9 @@ template <int NR, bool FULL>
 __device__ __forceinline__ void
 k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
           int32_t* __restrict__ out_stages, i64* __restrict__ out_bytes,
-          int32_t* __restrict__ out_num, i64* __restrict__ wsC, int S, int max_stages,
+          int32_t* __restrict__ out_num, i64* __restrict__ wsC, int S_arg, int max_stages,
           int b, int lane, unsigned char* k2_smem) {
+    const int S = FULL ? 64 * NR : S_arg;       // FULL: a compile-time constant
     u64* R = reinterpret_cast<u64*>(k2_smem);
     i64* PC = reinterpret_cast<i64*>(R + (size_t)S * S);
     i64* EC = PC + S;
