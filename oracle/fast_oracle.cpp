@@ -417,7 +417,12 @@ int decompose_bottleneck(int S, const i64* Q, const i64* A, int cap, int32_t* st
 //        factor is kept here.)
 //   if B_up < (G-1) B_out the redistributions no longer hide under the next
 //   stage; with sizes sorted ascending l_0 <= l_1 <= ... the exposed part
-//   sum_{i>=1} max(0, (G-1) l_{i-1}/B_up - l_i/B_out) is added (t_exc).
+//   sum_{i>=1} max(0, (G-1) l_{i-1}/B_up - l_i/B_out) is added (t_exc).  Reading:
+//   the proof's execution with a synchronisation between pipeline steps - step i
+//   moves stage i over scale-out while stage i-1 is redistributed, and ends when
+//   both have ended - so every overhang delays everything after it and an overhang
+//   is never absorbed by a later, longer stage (pipeline_time() below is the
+//   free-running pipeline of Section 4.3, where it can be).
 //   t_opt = max(max row sum, max column sum of T) / (G * B_out)   (Theorem 1).
 //   wake-up delay (Section 5.4: every transfer step costs a fixed link wake-up
 //   delay plus size/bandwidth): `delay` seconds are added once per executed step;

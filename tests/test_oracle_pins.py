@@ -249,24 +249,131 @@ def test_unit_handling(oracle):
     assert total / (N * p.time4[3]) == pytest.approx(50e9 / 0.75, rel=1e-12)
 
 
+def _stages_only(oracle, weights, G, B1, B2, S=2):
+    """cost() of a plan that consists of nothing but stages of the given weights (in the given
+    extraction order): no balancing, no intra-server bytes; server 0 sends the weight, the
+    others less.  Returns (T_pred, t2, t1, t3, t_exc)."""
+    N = S * G
+    z = np.zeros((N, N), dtype=np.int64)
+    sb = np.zeros((len(weights), S), dtype=np.int64)
+    sb[:, 0] = weights
+    sb[:, 1:] = np.asarray(weights, dtype=np.int64)[:, None] // 3
+    t4, e3 = oracle.cost(S, G, B1, B2, np.zeros((S, S), np.int64), z, np.zeros(N, np.int64),
+                         np.zeros(N, np.int64), sb)
+    return t4[0], t4[2], e3[0], e3[1], e3[2]
+
+
+def _barrier_replay(weights, G, B1, B2):
+    """Event replay of what the slow-scale-up reading means (Appendix, proof of Theorem 2, the
+    execution the steps (i)-(iii) describe, without the hiding condition): the stages run in
+    ascending size; pipeline step i moves stage i over scale-out while stage i-1 is
+    redistributed over scale-up ((G-1) l bytes); a step ends when both have ended, and the
+    next one starts then; after the last stage its redistribution runs alone."""
+    l = sorted(int(w) for w in weights)
+    now = 0.0
+    for i in range(len(l) + 1):
+        ends = [now]
+        if i < len(l):
+            ends.append(now + l[i] / B2)                   # scale-out of stage i
+        if i >= 1:
+            ends.append(now + (G - 1) * l[i - 1] / B1)     # redistribution of stage i-1
+        now = max(ends)
+    return now
+
+
+def test_exposed_redistribution_hand_cases(oracle):
+    # (a) three stages, extracted as 11, 1, 10; G = 4, B_up = 2, B_out = 1 (B_up < 3 B_out).
+    # Ascending: 1, 10, 11.  Redistribution of "1": 3*1/2 = 1.5 <= 10/1 -> hidden.
+    # Redistribution of "10": 3*10/2 = 15 > 11/1 -> 4 exposed.  t_exc = 4.
+    # t2 = 22/1, t3 = 3*11/2 = 16.5, T = 22 + 16.5 + 4 = 42.5.
+    T, t2, t1, t3, exc = _stages_only(oracle, [11, 1, 10], 4, 2.0, 1.0)
+    assert (t2, t1, t3, exc, T) == (22.0, 0.0, 16.5, 4.0, 42.5)
+    # (b) the same stages with a scale-up fabric that hides everything: B_up = 3 = (G-1) B_out
+    T, t2, t1, t3, exc = _stages_only(oracle, [11, 1, 10], 4, 3.0, 1.0)
+    assert (t2, t3, exc, T) == (22.0, 11.0, 0.0, 33.0)
+    # (c) equal weights, nothing hides: 1, 1, 1 with G = 4, B_up = B_out = 1: each of the two
+    # inner redistributions (3) overhangs the next stage (1) by 2 -> t_exc = 4, T = 3 + 3 + 4.
+    T, t2, t1, t3, exc = _stages_only(oracle, [1, 1, 1], 4, 1.0, 1.0)
+    assert (t2, t3, exc, T) == (3.0, 3.0, 4.0, 10.0)
+    # (d) an excess followed by slack: 1, 1, 10: redistribution of the first "1" overhangs the
+    # second by 2, that of the second (3) hides under "10".  t_exc = 2, T = 12 + 30 + 2 = 44.
+    T, t2, t1, t3, exc = _stages_only(oracle, [10, 1, 1], 4, 1.0, 1.0)
+    assert (t2, t3, exc, T) == (12.0, 30.0, 2.0, 44.0)
+    # a single stage has nothing to overhang
+    assert _stages_only(oracle, [7], 4, 1.0, 1.0)[4] == 0.0
+
+
+def test_exposed_redistribution_uniform_all_to_all(oracle):
+    # S = 3, G = 4, 25 bytes per GPU pair: every tile holds 16 * 25 = 400 bytes, 100 per lane;
+    # two stages of weight 100 (Section 4.4 "Number of stages").  B_up = 20 = 2 B_out < 3 B_out:
+    # t_exc = (K-1) * (3*100/20 - 100/10) = 15 - 10 = 5; t2 = 200/10 = 20; t3 = 300/20 = 15;
+    # t1 = 3 peers * 25 / 20 = 3.75; t0 = 0.  T = 3.75 + 20 + 15 + 5 = 43.75.
+    S, G = 3, 4
+    N = S * G
+    t = np.full((N, N), 25, dtype=np.int64)
+    np.fill_diagonal(t, 0)
+    p = oracle.synthesize(S, G, 20.0, 10.0, t)
+    assert p.K == 2 and (p.stage_bytes.max(axis=1) == 100).all()
+    assert p.extra3[2] == 5.0
+    assert tuple(p.time4[:3]) == (43.75, 0.0, 20.0) and p.extra3[0] == 3.75 and p.extra3[1] == 15.0
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_exposed_redistribution_is_the_barrier_synchronised_pipeline(oracle, seed):
+    # t2 + t3 + t_exc must be the end of the event replay above, on random weights and on
+    # bandwidth ratios on both sides of the hiding condition
+    rng = np.random.default_rng(100 + seed)
+    G = int(rng.integers(2, 9))
+    K = int(rng.integers(1, 9))
+    w = rng.integers(1, 1000, size=K).tolist()
+    B2 = 1.0
+    for B1 in (0.25, 1.0, float(G - 1) - 0.5, float(G - 1), 3.0 * G):
+        T, t2, t1, t3, exc = _stages_only(oracle, w, G, B1, B2)
+        want = _barrier_replay(w, G, B1, B2)
+        if B1 >= (G - 1) * B2:
+            assert exc == 0.0
+        assert t2 + t3 + exc == pytest.approx(want, rel=1e-12)
+        assert T == pytest.approx(want, rel=1e-12)
+
+
+def test_barrier_pipeline_is_never_faster_than_the_free_running_one(oracle):
+    # The overlapped pipeline of Section 4.3 (pipeline_time: scale-out stages back to back, the
+    # fabric taking the redistributions as they come) differs from the barrier-synchronised
+    # reading exactly when an excess is followed by slack: on 1, 1, 10 (G = 4, both bandwidths
+    # 1) the scale-out stages end at 1, 2, 12 and the fabric runs 1-4, 4-7, 12-42: 42 against 44.
+    S, G = 2, 4
+    N = S * G
+    z = np.zeros((N, N), dtype=np.int64)
+    zi = np.zeros(N, dtype=np.int64)
+    sb = np.zeros((3, S), dtype=np.int64)
+    sb[:, 0] = [1, 1, 10]
+    free = oracle.pipeline_time(S, G, 1.0, 1.0, z, sb)
+    assert tuple(free) == (42.0, 12.0)
+    assert _stages_only(oracle, [1, 1, 10], G, 1.0, 1.0)[0] == 44.0
+    rng = np.random.default_rng(5)
+    for _ in range(20):
+        K = int(rng.integers(1, 7))
+        sb = np.zeros((K, S), dtype=np.int64)
+        sb[:, 0] = np.sort(rng.integers(1, 50, size=K))
+        B1 = float(rng.choice([0.5, 1.0, 2.0, 5.0]))
+        assert _stages_only(oracle, sb[:, 0].tolist(), G, B1, 1.0)[0] >= \
+            oracle.pipeline_time(S, G, B1, 1.0, z, sb)[0] - 1e-12
+
+
 def test_exposed_redistribution_when_scale_up_is_slow(oracle):
-    # Proof of Theorem 2, step (iii): hiding needs B_up >= (G-1) B_out.  Below that the
-    # exposed part is added; check against a direct evaluation on the stage weights.
+    # Through the whole path on a skewed matrix: the term is there when B_up < (G-1) B_out,
+    # absent otherwise, and T_pred is the sum of its parts.
     S, G = 5, 8
     rng = np.random.default_rng(3)
     t = _rand_traffic(rng, S, G, "heavy")
     B1, B2 = 100.0, 50.0
     p = oracle.synthesize(S, G, B1, B2, t)
-    c = np.sort(p.stage_bytes.max(axis=1))
-    exc = 0.0
-    for i in range(1, len(c)):
-        exc += max(0.0, (G - 1) * int(c[i - 1]) / B1 - int(c[i]) / B2)
-    assert exc > 0
-    assert p.extra3[2] == pytest.approx(exc, rel=1e-12)
+    want = _barrier_replay(p.stage_bytes.max(axis=1), G, B1, B2)
+    assert p.extra3[2] > 0
+    assert p.time4[2] + p.extra3[1] + p.extra3[2] == pytest.approx(want, rel=1e-12)
     fast = oracle.synthesize(S, G, 7 * B2, B2, t)
     assert fast.extra3[2] == 0.0
-    assert p.time4[0] == pytest.approx(p.time4[1] + p.extra3[0] + p.time4[2] + p.extra3[1] + exc,
-                                       rel=1e-12)
+    assert p.time4[0] == pytest.approx(p.time4[1] + p.extra3[0] + want, rel=1e-12)
 
 
 # ---------------------------------------------------------------- workloads feed the oracle

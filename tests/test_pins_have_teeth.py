@@ -64,6 +64,15 @@ MUTATIONS = [
     ("exposed redistribution never added",
      "if (bw_up < (double)(G - 1) * bw_out) {",
      "if (false) {"),
+    ("exposed redistribution pairs a stage with the wrong neighbour",
+     "const double redis = (double)((i64)(G - 1) * c[i - 1]) / bw_up;\n            const double next = (double)c[i] / bw_out;",
+     "const double redis = (double)((i64)(G - 1) * c[i]) / bw_up;\n            const double next = (double)c[i - 1] / bw_out;"),
+    ("exposed redistribution evaluated in extraction order",
+     "std::sort(c.begin(), c.end());\n        for (int i = 1; i < K; ++i) {",
+     "for (int i = 1; i < K; ++i) {"),
+    ("exposed redistribution without its (G-1) factor",
+     "const double redis = (double)((i64)(G - 1) * c[i - 1]) / bw_up;",
+     "const double redis = (double)c[i - 1] / bw_up;"),
     ("wake-up delay not paid per stage",
      "(K > 0 ? K : 0) +",
      "0 +"),
@@ -126,6 +135,9 @@ def battery(O):
     TP.test_zero_and_single_cell(O)
     TP.test_theorem2_terms_on_adversarial_input(O)
     TP.test_unit_handling(O)
+    TP.test_exposed_redistribution_hand_cases(O)
+    TP.test_exposed_redistribution_uniform_all_to_all(O)
+    TP.test_exposed_redistribution_is_the_barrier_synchronised_pipeline(O, 0)
     TP.test_exposed_redistribution_when_scale_up_is_slow(O)
     for S, G, kind in [(3, 2, "heavy"), (4, 8, "sparse"), (5, 7, "uniform")]:
         TP.test_invariants_random(O, S, G, kind)
