@@ -36,13 +36,16 @@ extern "C" {
 #endif
 
 #define FAST_OK                0
-#define FAST_ERR_INVALID_ARG  -1   /* NULL pointer, B < 0, S < 1, G < 1, bandwidth not finite or <= 0 */
-#define FAST_ERR_UNSUPPORTED  -2   /* S > FAST_MAX_SERVERS or G > FAST_MAX_GPUS_PER_SERVER */
+#define FAST_ERR_INVALID_ARG  -1   /* NULL pointer, B < 0, S < 1, G < 1, bandwidth not finite or <= 0,
+                                      or the plan's device is not the current HIP device */
+#define FAST_ERR_UNSUPPORTED  -2   /* S > FAST_MAX_SERVERS, G > FAST_MAX_GPUS_PER_SERVER, or a batch of
+                                      more than FAST_MAX_BATCH matrices (or selections) in one call */
 #define FAST_ERR_HIP          -3   /* a HIP runtime call failed */
 #define FAST_ERR_OOM          -4   /* the plan's device workspace could not be allocated */
 
 #define FAST_MAX_SERVERS          128
 #define FAST_MAX_GPUS_PER_SERVER  8
+#define FAST_MAX_BATCH            65535   /* matrices per call (a launch-grid dimension) */
 
 /* Per-matrix status values stored in out_num_stages[b] instead of a stage count. */
 #define FAST_STATUS_NEGATIVE_ENTRY  -1  /* an off-diagonal traffic entry is negative */
@@ -67,11 +70,16 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
 int fast_plan_max_stages(const fast_plan_t *plan);
 
 /*
- * Synthesises the schedules of B traffic matrices.  All work is enqueued on
- * `stream` (the plan's device must be current) and the call returns without
- * synchronising; outputs are valid once the stream has drained.  The plan's
- * workspace is grown on demand (the only allocation this call may make) and is
- * reused by the next call, so calls on one plan must be stream-ordered.
+ * Synthesises the schedules of B traffic matrices (B <= FAST_MAX_BATCH).  All work is
+ * enqueued on `stream` (the plan's device must be current: FAST_ERR_INVALID_ARG otherwise)
+ * and the call returns without synchronising; outputs are valid once the stream has
+ * drained.  The plan's workspace is reused by the next call, so calls on one plan must be
+ * stream-ordered.  It is grown on demand, the only allocation this call may make: a call
+ * with a larger B than any before on this plan (the first call included) frees the old
+ * workspace and allocates a new one, which synchronises the device, must not happen while
+ * a stream is being captured, and leaves any HIP graph captured from earlier calls on this
+ * plan pointing at freed memory.  Make one call with the largest B first to avoid all three;
+ * the analysis entry points below treat their own parts of the workspace the same way.
  *
  *  traffic            device, [B][N][N] row-major; traffic[b][g][h] = bytes GPU g sends to
  *                     GPU h (row = sender, Section 4.1 "Example setup").  The GPU diagonal
@@ -99,6 +107,14 @@ int fast_plan_max_stages(const fast_plan_t *plan);
  *                     link_bw_up < (G-1)*link_bw_out) with t1 = intra-server portion and
  *                     t3 = last stage's redistribution (Appendix, proof of Theorem 2, the
  *                     four terms evaluated on the actual plan); t_opt = Theorem 1.
+ *                     t3 = (G-1) * largest stage weight / link_bw_up: step (i) of that proof
+ *                     prices a stage's redistribution at (m-1) l / B_1 (every GPU of the
+ *                     destination server forwards all it received to one GPU) while the t3
+ *                     printed after it has lost the (m-1); the factor of step (i) is kept.
+ *                     The exposed part is sum over i >= 1 of max(0, (G-1) l_{i-1} / link_bw_up
+ *                     - l_i / link_bw_out) on the stage weights in ascending order: pipeline
+ *                     step i (stage i on scale-out, stage i-1 redistributed) ends when both
+ *                     have ended.
  *
  * Results are a deterministic function of each matrix alone: independent of B, of the
  * position in the batch and of launch geometry.  B == 0 is valid and does nothing.
@@ -266,19 +282,41 @@ int fast_redistribution_matrices(fast_plan_t *plan, int B, const int64_t *traffi
  * has ended and the scale-up fabric is free (one transfer at a time: the intra-server portion,
  * then the redistributions in stage order); the last redistribution is exposed.  Each step that
  * moves bytes costs the wake-up delay plus bytes / bandwidth.
- * Evaluates the plans of the most recent fast_synthesize_batched call on this plan, which must
- * have been made with the same B (the balancing and intra-server volumes and the stage weights
- * are taken from the plan's workspace); FAST_ERR_INVALID_ARG otherwise.
- *   num_stages         device, [B], as written by that call
+ * Everything it evaluates is passed in; the plan contributes S, G, the bandwidths and the delay.
+ *   stage_weight       device, [B][max_stages] int64; [b][s] = weight of stage s (largest per-lane
+ *                      byte count of the stage), as written by fast_plan_summary_batched
+ *   scaleup_bytes      device, [B][2] int64 = { balancing volume, intra-server volume } (the
+ *                      numerators of t0 and t1), as written by fast_plan_summary_batched
+ *   num_stages         device, [B], as written by fast_synthesize_batched; a count above
+ *                      max_stages is read as max_stages
  *   stage_order        device, [B][max_stages], or NULL = extraction order
  *   redis_bytes        device, [B][max_stages] as written by fast_redistribution_batched, or NULL
  *                      = the Appendix's worst case (G-1) * stage weight
  *   out_pipeline_time  device, [B][2] seconds = { completion time, end of the last scale-out
  *                      stage }; both 0 for a matrix with negative num_stages
  */
-int fast_pipeline_time_batched(fast_plan_t *plan, int B, const int32_t *num_stages,
+int fast_pipeline_time_batched(fast_plan_t *plan, int B, const int64_t *stage_weight,
+                               const int64_t *scaleup_bytes, const int32_t *num_stages,
                                const int32_t *stage_order, const int64_t *redis_bytes,
                                double *out_pipeline_time, hipStream_t stream);
+
+/*
+ * Copies out what the completion-time models need of the plans of the most recent
+ * fast_synthesize_batched call on this plan (Appendix, proof of Theorem 2: the balancing and
+ * intra-server volumes behind t0 and t1 and the stage sizes l_i), so that
+ * fast_pipeline_time_batched can be given them explicitly.  Call it on the same stream right
+ * after the synthesis call whose plans it describes: B has to be that call's B
+ * (FAST_ERR_INVALID_ARG otherwise), and a later synthesis call on the plan replaces what it
+ * would copy.
+ *   out_stage_weight   device, [B][max_stages] int64; entries 0..K-1 = stage weights in
+ *                      extraction order, entries >= K unspecified
+ *   out_scaleup_bytes  device, [B][2] int64 = { largest over the GPUs of max(bytes handed off,
+ *                      bytes handed in) by the balancing, largest over the GPUs of
+ *                      max(intra-server bytes out, in) }
+ * Unspecified for a matrix whose num_stages is negative.  Enqueued on `stream`, asynchronous.
+ */
+int fast_plan_summary_batched(fast_plan_t *plan, int B, int64_t *out_stage_weight,
+                              int64_t *out_scaleup_bytes, hipStream_t stream);
 
 /*
  * Per-kernel timing for measurement.  fast_plan_set_timing(plan, 1) starts a new

@@ -6,6 +6,7 @@ exception is raised.  PyTorch is used for device memory and streams.
 """
 import ctypes
 import os
+import weakref
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfast.so")
@@ -17,6 +18,7 @@ FAST_ERR_HIP = -3
 FAST_ERR_OOM = -4
 FAST_MAX_SERVERS = 128
 FAST_MAX_GPUS_PER_SERVER = 8
+FAST_MAX_BATCH = 65535
 FAST_STATUS_NEGATIVE_ENTRY = -1
 FAST_STATUS_STAGE_OVERFLOW = -2
 FAST_STATUS_INTERNAL = -3
@@ -25,7 +27,7 @@ EXPORTS = ("fast_plan_create", "fast_plan_max_stages", "fast_synthesize_batched"
            "fast_plan_set_wakeup_delay", "fast_plan_set_matching", "fast_spreadout_batched", "fast_build_traffic_batched",
            "fast_stage_order_batched", "fast_stage_offsets_batched",
            "fast_redistribution_batched", "fast_redistribution_matrices",
-           "fast_pipeline_time_batched",
+           "fast_pipeline_time_batched", "fast_plan_summary_batched",
            "fast_plan_set_timing", "fast_plan_timed_calls", "fast_plan_kernel_ms",
            "fast_plan_destroy")
 
@@ -73,8 +75,10 @@ def lib():
         L.fast_redistribution_matrices.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp,
                                                    ctypes.c_int, vp, vp, vp]
         L.fast_redistribution_matrices.restype = ctypes.c_int
-        L.fast_pipeline_time_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp]
+        L.fast_pipeline_time_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp]
         L.fast_pipeline_time_batched.restype = ctypes.c_int
+        L.fast_plan_summary_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp]
+        L.fast_plan_summary_batched.restype = ctypes.c_int
         L.fast_plan_set_timing.argtypes = [vp, ctypes.c_int]
         L.fast_plan_set_timing.restype = ctypes.c_int
         L.fast_plan_timed_calls.argtypes = [vp]
@@ -180,13 +184,20 @@ def fast_redistribution_matrices(plan, B, traffic, rebalance, stages, stage_byte
         raise FastError("fast_redistribution_matrices", rc)
 
 
-def fast_pipeline_time_batched(plan, B, num_stages, stage_order, redis_bytes, out_pipeline_time,
-                               stream):
+def fast_pipeline_time_batched(plan, B, stage_weight, scaleup_bytes, num_stages, stage_order,
+                               redis_bytes, out_pipeline_time, stream):
     """Raw call: buffer arguments are device addresses (int; stage_order, redis_bytes may be None)."""
-    rc = lib().fast_pipeline_time_batched(plan, int(B), num_stages, stage_order, redis_bytes,
-                                          out_pipeline_time, stream)
+    rc = lib().fast_pipeline_time_batched(plan, int(B), stage_weight, scaleup_bytes, num_stages,
+                                          stage_order, redis_bytes, out_pipeline_time, stream)
     if rc != FAST_OK:
         raise FastError("fast_pipeline_time_batched", rc)
+
+
+def fast_plan_summary_batched(plan, B, out_stage_weight, out_scaleup_bytes, stream):
+    """Raw call: buffer arguments are device addresses (int)."""
+    rc = lib().fast_plan_summary_batched(plan, int(B), out_stage_weight, out_scaleup_bytes, stream)
+    if rc != FAST_OK:
+        raise FastError("fast_plan_summary_batched", rc)
 
 
 def fast_plan_set_timing(plan, enable):
@@ -223,6 +234,9 @@ class Outputs:
         self.stage_bytes = torch.empty((B, max_stages, S), dtype=torch.int64, device=device)
         self.num_stages = torch.empty((B,), dtype=torch.int32, device=device)
         self.predicted_time = torch.empty((B, 4), dtype=torch.float64, device=device)
+        # filled by Synthesizer.summary(): what fast_pipeline_time_batched is given explicitly
+        self.stage_weight = None
+        self.scaleup_bytes = None
 
 
 class Synthesizer:
@@ -235,6 +249,7 @@ class Synthesizer:
         with torch.cuda.device(self.device):
             self.plan = fast_plan_create(S, G, link_bw_up, link_bw_out)
         self.max_stages = fast_plan_max_stages(self.plan)
+        self._last_out = None       # weak reference to the Outputs of the latest synthesize()
 
     def alloc_outputs(self, B):
         return Outputs(B, self.S, self.G, self.max_stages, self.device)
@@ -255,6 +270,9 @@ class Synthesizer:
                                     out.stages.data_ptr(), out.stage_bytes.data_ptr(),
                                     out.num_stages.data_ptr(), out.predicted_time.data_ptr(),
                                     stream)
+        # the plans in `out` are new: a summary taken for its previous contents is stale
+        out.stage_weight = out.scaleup_bytes = None
+        self._last_out = weakref.ref(out)
         return out
 
     def set_wakeup_delay(self, seconds):
@@ -303,7 +321,7 @@ class Synthesizer:
         stage_order(), or None = extraction order) -> int64 tensor [B, max_stages, S]."""
         import torch
         B = out.num_stages.shape[0]
-        off = torch.zeros((B, self.max_stages, self.S), dtype=torch.int64, device=self.device)
+        off = torch.empty((B, self.max_stages, self.S), dtype=torch.int64, device=self.device)
         with torch.cuda.device(self.device):
             fast_stage_offsets_batched(self.plan, B, out.stages.data_ptr(), out.stage_bytes.data_ptr(),
                                        out.num_stages.data_ptr(),
@@ -316,7 +334,7 @@ class Synthesizer:
         [B, max_stages, S], redis_bytes int64 [B, max_stages])."""
         import torch
         B = out.num_stages.shape[0]
-        off = torch.zeros((B, self.max_stages, self.S), dtype=torch.int64, device=self.device)
+        off = torch.empty((B, self.max_stages, self.S), dtype=torch.int64, device=self.device)
         rb = torch.empty((B, self.max_stages), dtype=torch.int64, device=self.device)
         with torch.cuda.device(self.device):
             fast_redistribution_batched(self.plan, B, traffic.data_ptr(), out.rebalance.data_ptr(),
@@ -341,14 +359,35 @@ class Synthesizer:
                                          sel.data_ptr(), mats.data_ptr(), self._stream())
         return mats
 
-    def pipeline_time(self, out, order=None, redis_bytes=None):
-        """Overlapped-pipeline completion time of the plans of the last synthesize() call
-        -> float64 tensor [B, 2] (completion time, end of the last scale-out stage)."""
+    def summary(self, out):
+        """Copies the stage weights and the two scale-up volumes of the plans in `out` out of the
+        plan's workspace into out.stage_weight [B, max_stages] / out.scaleup_bytes [B, 2].  `out`
+        has to be what the most recent synthesize() call on this object wrote."""
         import torch
+        if self._last_out is None or self._last_out() is not out:
+            raise ValueError("summary() describes the most recent synthesize() call only: "
+                             "call it before synthesising another batch")
+        B = out.num_stages.shape[0]
+        if out.stage_weight is None:
+            out.stage_weight = torch.empty((B, self.max_stages), dtype=torch.int64, device=self.device)
+            out.scaleup_bytes = torch.empty((B, 2), dtype=torch.int64, device=self.device)
+        with torch.cuda.device(self.device):
+            fast_plan_summary_batched(self.plan, B, out.stage_weight.data_ptr(),
+                                      out.scaleup_bytes.data_ptr(), self._stream())
+        return out.stage_weight, out.scaleup_bytes
+
+    def pipeline_time(self, out, order=None, redis_bytes=None):
+        """Overlapped-pipeline completion time of the plans in `out` -> float64 tensor [B, 2]
+        (completion time, end of the last scale-out stage).  Needs out.stage_weight and
+        out.scaleup_bytes: taken with summary() now if `out` is still the latest batch."""
+        import torch
+        if out.stage_weight is None:
+            self.summary(out)
         B = out.num_stages.shape[0]
         t = torch.empty((B, 2), dtype=torch.float64, device=self.device)
         with torch.cuda.device(self.device):
-            fast_pipeline_time_batched(self.plan, B, out.num_stages.data_ptr(),
+            fast_pipeline_time_batched(self.plan, B, out.stage_weight.data_ptr(),
+                                       out.scaleup_bytes.data_ptr(), out.num_stages.data_ptr(),
                                        order.data_ptr() if order is not None else None,
                                        redis_bytes.data_ptr() if redis_bytes is not None else None,
                                        t.data_ptr(), self._stream())

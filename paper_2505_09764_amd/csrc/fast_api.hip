@@ -56,6 +56,14 @@ struct fast_plan {
 
 namespace {
 
+// The four workspace arrays of a synthesis call for B matrices, wherever they live.
+struct synth_workspace {
+    i64* T;      // [B][S][S]  server-to-server totals
+    i64* Q;      // [B][S][S]  per-lane server-level matrix
+    i64* Part;   // [B][S][K1_PART]
+    i64* C;      // [B][max_stages] stage weights
+};
+
 void free_workspace(fast_plan* p) {
     if (p->wsT) (void)hipFree(p->wsT);
     p->wsT = p->wsQ = p->wsPart = p->wsC = nullptr;
@@ -127,7 +135,8 @@ int grow_workspace(fast_plan* p, int B) {
 static_assert(fastk::K1_MAX_S == FAST_MAX_SERVERS, "kernel 1 unrolls for FAST_MAX_SERVERS");
 
 template <int G>
-void launch_k1(const fast_plan* p, int B, const i64* traffic, i64* X, hipStream_t stream) {
+void launch_k1(const fast_plan* p, const synth_workspace& ws, int B, const i64* traffic, i64* X,
+               hipStream_t stream) {
     const dim3 grid(p->S, B), block(fastk::K1_THREADS);
     const size_t lds = fastk::k1_lds_bytes(p->S, G);
     const bool vec = (G % 2 == 0) && ((reinterpret_cast<uintptr_t>(traffic) |
@@ -135,19 +144,19 @@ void launch_k1(const fast_plan* p, int B, const i64* traffic, i64* X, hipStream_
     if constexpr (G == 2 || G == 4 || G == 8) {
         if (vec) {
             hipLaunchKernelGGL((fastk::k1_rebalance_tiles<G>), grid, block,
-                               fastk::k1_tiles_lds_bytes(G), stream, traffic, X, p->wsT, p->wsQ,
-                               p->wsPart, p->S);
+                               fastk::k1_tiles_lds_bytes(G), stream, traffic, X, ws.T, ws.Q,
+                               ws.Part, p->S);
             return;
         }
     } else if constexpr (G % 2 == 0) {
         if (vec) {
             hipLaunchKernelGGL((fastk::k1_rebalance<G, true>), grid, block, lds, stream, traffic,
-                               X, p->wsT, p->wsQ, p->wsPart, p->S);
+                               X, ws.T, ws.Q, ws.Part, p->S);
             return;
         }
     }
     hipLaunchKernelGGL((fastk::k1_rebalance<G, false>), grid, block, lds, stream, traffic, X,
-                       p->wsT, p->wsQ, p->wsPart, p->S);
+                       ws.T, ws.Q, ws.Part, p->S);
 }
 
 
@@ -165,10 +174,68 @@ rd_offsets_fn rd_offsets_kernel(int S, bool lists, bool ordered) {
     return all ? &fastk::rd_offsets<false, false, true> : &fastk::rd_offsets<false, false, false>;
 }
 
+// FAST_OK if the plan's device is the current one (the kernels would otherwise be launched
+// on another GPU than the one that holds the workspace), else the error to return.
+int check_device(const fast_plan* p) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return FAST_ERR_HIP;
+    }
+    return dev == p->device ? FAST_OK : FAST_ERR_INVALID_ARG;
+}
+
 int next_pow2(int v) {
     int n = 1;
     while (n < v) n <<= 1;
     return n;
+}
+
+// Enqueues the kernels of one synthesis call (aggregation + balancing, decomposition, cost
+// model) on `stream`; ev = four events to record around them, or nullptr.
+void enqueue_synthesis(const fast_plan* p, const synth_workspace& ws, int B, const int64_t* traffic,
+                       int64_t* out_rebalance, int32_t* out_stages, int64_t* out_stage_bytes,
+                       int32_t* out_num_stages, double* out_predicted_time, hipEvent_t* ev,
+                       hipStream_t stream) {
+    if (ev) (void)hipEventRecord(ev[0], stream);
+    const i64* tr = reinterpret_cast<const i64*>(traffic);
+    i64* X = reinterpret_cast<i64*>(out_rebalance);
+    switch (p->G) {
+        case 1: launch_k1<1>(p, ws, B, tr, X, stream); break;
+        case 2: launch_k1<2>(p, ws, B, tr, X, stream); break;
+        case 3: launch_k1<3>(p, ws, B, tr, X, stream); break;
+        case 4: launch_k1<4>(p, ws, B, tr, X, stream); break;
+        case 5: launch_k1<5>(p, ws, B, tr, X, stream); break;
+        case 6: launch_k1<6>(p, ws, B, tr, X, stream); break;
+        case 7: launch_k1<7>(p, ws, B, tr, X, stream); break;
+        default: launch_k1<8>(p, ws, B, tr, X, stream); break;
+    }
+    if (ev) (void)hipEventRecord(ev[1], stream);
+
+    i64* sb = reinterpret_cast<i64*>(out_stage_bytes);
+    const bool slow_up = p->bw_up < (double)(p->G - 1) * p->bw_out;
+    const int sort_n = slow_up ? next_pow2(p->max_stages) : 0;
+    // Small clusters are bound by the launches: there the cost model rides on the decomposition
+    // kernel's wavefront (about 3 us less per call), unless it has to sort the stage weights
+    // (slow scale-up fabric) or the fewer-stages kernel is in use.  On large clusters one
+    // wavefront takes longer over the model's reductions than kernel 3's launch costs.
+    const bool with_cost =
+        p->matching == FAST_MATCHING_SUPPORT && sort_n == 0 && p->S <= fastk::K2_COST_MAX_S;
+    if (p->matching == FAST_MATCHING_BOTTLENECK)
+        fastk::launch_k9(p->S, B, stream, ws.Q, ws.Part, out_stages, sb, out_num_stages, ws.C,
+                         p->max_stages);
+    else
+        fastk::launch_k2(p->S, with_cost, B, stream, ws.Q, ws.Part, out_stages, sb,
+                         out_num_stages, ws.C, p->max_stages, ws.T, out_predicted_time, p->G,
+                         p->bw_up, p->bw_out, p->delay);
+    if (ev) (void)hipEventRecord(ev[2], stream);
+
+    if (!with_cost)
+        hipLaunchKernelGGL(fastk::k3_cost, dim3(B), dim3(fastk::K3_THREADS),
+                           (size_t)sort_n * sizeof(i64), stream, ws.T, ws.Part, ws.C,
+                           out_num_stages, out_predicted_time, p->S, p->G, p->max_stages, p->bw_up,
+                           p->bw_out, p->delay, sort_n);
+    if (ev) (void)hipEventRecord(ev[3], stream);
 }
 
 }  // namespace
@@ -245,8 +312,10 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
     if (!traffic || !out_rebalance || !out_stages || !out_stage_bytes || !out_num_stages ||
         !out_predicted_time)
         return FAST_ERR_INVALID_ARG;
-    if (B > 65535) return FAST_ERR_UNSUPPORTED;     // grid.y limit of the first kernel
-    const int rc = grow_workspace(p, B);
+    if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;     // grid.y limit of the first kernel
+    int rc = check_device(p);
+    if (rc != FAST_OK) return rc;
+    rc = grow_workspace(p, B);
     if (rc != FAST_OK) return rc;
 
     hipEvent_t* ev = nullptr;
@@ -261,50 +330,11 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
                 (void)hipGetLastError();
                 return FAST_ERR_HIP;
             }
-        (void)hipEventRecord(ev[0], stream);
     }
-
-    const i64* tr = reinterpret_cast<const i64*>(traffic);
-    i64* X = reinterpret_cast<i64*>(out_rebalance);
-    switch (p->G) {
-        case 1: launch_k1<1>(p, B, tr, X, stream); break;
-        case 2: launch_k1<2>(p, B, tr, X, stream); break;
-        case 3: launch_k1<3>(p, B, tr, X, stream); break;
-        case 4: launch_k1<4>(p, B, tr, X, stream); break;
-        case 5: launch_k1<5>(p, B, tr, X, stream); break;
-        case 6: launch_k1<6>(p, B, tr, X, stream); break;
-        case 7: launch_k1<7>(p, B, tr, X, stream); break;
-        default: launch_k1<8>(p, B, tr, X, stream); break;
-    }
-    if (ev) (void)hipEventRecord(ev[1], stream);
-
-    i64* sb = reinterpret_cast<i64*>(out_stage_bytes);
-    const bool slow_up = p->bw_up < (double)(p->G - 1) * p->bw_out;
-    const int sort_n = slow_up ? next_pow2(p->max_stages) : 0;
-    // Small clusters are bound by the launches: there the cost model rides on the decomposition
-    // kernel's wavefront (about 3 us less per call), unless it has to sort the stage weights
-    // (slow scale-up fabric) or the fewer-stages kernel is in use.  On large clusters one
-    // wavefront takes longer over the model's reductions than kernel 3's launch costs.
-    const bool with_cost =
-        p->matching == FAST_MATCHING_SUPPORT && sort_n == 0 && p->S <= fastk::K2_COST_MAX_S;
-    if (p->matching == FAST_MATCHING_BOTTLENECK)
-        fastk::launch_k9(p->S, B, stream, p->wsQ, p->wsPart, out_stages, sb, out_num_stages, p->wsC,
-                         p->max_stages);
-    else
-        fastk::launch_k2(p->S, with_cost, B, stream, p->wsQ, p->wsPart, out_stages, sb,
-                         out_num_stages, p->wsC, p->max_stages, p->wsT, out_predicted_time, p->G,
-                         p->bw_up, p->bw_out, p->delay);
-    if (ev) (void)hipEventRecord(ev[2], stream);
-
-    if (!with_cost)
-        hipLaunchKernelGGL(fastk::k3_cost, dim3(B), dim3(fastk::K3_THREADS),
-                           (size_t)sort_n * sizeof(i64), stream, p->wsT, p->wsPart, p->wsC,
-                           out_num_stages, out_predicted_time, p->S, p->G, p->max_stages, p->bw_up,
-                           p->bw_out, p->delay, sort_n);
-    if (ev) {
-        (void)hipEventRecord(ev[3], stream);
-        ++p->n_timed;
-    }
+    const synth_workspace ws = {p->wsT, p->wsQ, p->wsPart, p->wsC};
+    enqueue_synthesis(p, ws, B, traffic, out_rebalance, out_stages, out_stage_bytes, out_num_stages,
+                      out_predicted_time, ev, stream);
+    if (ev) ++p->n_timed;
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     p->last_B = B;
     return FAST_OK;
@@ -328,8 +358,10 @@ int fast_spreadout_batched(fast_plan_t* p, int B, const int64_t* traffic,
     if (!p || B < 0) return FAST_ERR_INVALID_ARG;
     if (B == 0) return FAST_OK;
     if (!traffic || !out_spreadout_time) return FAST_ERR_INVALID_ARG;
-    if (B > 65535) return FAST_ERR_UNSUPPORTED;
-    const int rc = grow_spo_workspace(p, B);
+    if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
+    int rc = check_device(p);
+    if (rc != FAST_OK) return rc;
+    rc = grow_spo_workspace(p, B);
     if (rc != FAST_OK) return rc;
     const int N = p->S * p->G;
     const int CS = fastk::spo_chunk_servers(p->S, p->G);
@@ -364,7 +396,8 @@ int fast_stage_order_batched(fast_plan_t* p, int B, const int64_t* stage_bytes,
     if (!p || B < 0) return FAST_ERR_INVALID_ARG;
     if (B == 0) return FAST_OK;
     if (!stage_bytes || !num_stages || !out_stage_order) return FAST_ERR_INVALID_ARG;
-    if (B > 65535) return FAST_ERR_UNSUPPORTED;
+    if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
+    if (const int rc = check_device(p); rc != FAST_OK) return rc;
     const int P = next_pow2(p->max_stages);
     if (B > p->so_cap_B) {
         if (p->soKeys) (void)hipFree(p->soKeys);
@@ -396,7 +429,8 @@ int fast_build_traffic_batched(fast_plan_t* p, int B, int E, const int64_t* toke
     if (B == 0) return FAST_OK;
     if (!tokens_per_expert || !expert_to_gpu || !out_traffic || !out_status)
         return FAST_ERR_INVALID_ARG;
-    if (B > 65535) return FAST_ERR_UNSUPPORTED;
+    if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
+    if (const int rc = check_device(p); rc != FAST_OK) return rc;
     const int N = p->S * p->G;
     hipLaunchKernelGGL(fastk::bt_zero, dim3((B + 255) / 256), dim3(256), 0, stream, out_status, B);
     hipLaunchKernelGGL(fastk::bt_build, dim3(N, B), dim3(fastk::BT_THREADS),
@@ -414,7 +448,8 @@ int fast_stage_offsets_batched(fast_plan_t* p, int B, const int32_t* stages,
     if (!p || B < 0) return FAST_ERR_INVALID_ARG;
     if (B == 0) return FAST_OK;
     if (!stages || !stage_bytes || !num_stages || !out_stage_offset) return FAST_ERR_INVALID_ARG;
-    if (B > 65535) return FAST_ERR_UNSUPPORTED;
+    if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
+    if (const int rc = check_device(p); rc != FAST_OK) return rc;
     const dim3 grid((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS, B);
     auto kern = rd_offsets_kernel(p->S, false, stage_order != nullptr);
     hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S, false),
@@ -435,7 +470,8 @@ int fast_redistribution_batched(fast_plan_t* p, int B, const int64_t* traffic,
     if (!traffic || !rebalance || !stages || !stage_bytes || !num_stages || !out_stage_offset ||
         !out_redis_bytes)
         return FAST_ERR_INVALID_ARG;
-    if (B > 65535) return FAST_ERR_UNSUPPORTED;
+    if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
+    if (const int rc = check_device(p); rc != FAST_OK) return rc;
     const size_t S = p->S, M = p->max_stages;
     if (B > p->rd_cap_B) {
         if (p->rdList) (void)hipFree(p->rdList);
@@ -482,7 +518,8 @@ int fast_redistribution_matrices(fast_plan_t* p, int B, const int64_t* traffic,
     if (!traffic || !rebalance || !stages || !stage_bytes || !num_stages || !stage_offset || !sel ||
         !out_matrices)
         return FAST_ERR_INVALID_ARG;
-    if (n_sel > 65535) return FAST_ERR_UNSUPPORTED;     // grid.y limit
+    if (n_sel > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;     // grid.y limit
+    if (const int rc = check_device(p); rc != FAST_OK) return rc;
     const size_t n = (size_t)n_sel * p->S * p->G * p->G;
     hipLaunchKernelGGL(fastk::rd_zero, dim3((unsigned)((n + 255) / 256 < 2048 ? (n + 255) / 256
                                                                             : 2048)),
@@ -496,16 +533,36 @@ int fast_redistribution_matrices(fast_plan_t* p, int B, const int64_t* traffic,
     return FAST_OK;
 }
 
-int fast_pipeline_time_batched(fast_plan_t* p, int B, const int32_t* num_stages,
+int fast_plan_summary_batched(fast_plan_t* p, int B, int64_t* out_stage_weight,
+                              int64_t* out_scaleup_bytes, hipStream_t stream) {
+    if (!p || B < 0) return FAST_ERR_INVALID_ARG;
+    if (B == 0) return FAST_OK;
+    if (!out_stage_weight || !out_scaleup_bytes) return FAST_ERR_INVALID_ARG;
+    if (B != p->last_B) return FAST_ERR_INVALID_ARG;    // no synthesis call of this size to summarise
+    if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
+    if (const int rc = check_device(p); rc != FAST_OK) return rc;
+    const int blocks = (p->max_stages + fastk::PL_THREADS - 1) / fastk::PL_THREADS + 1;
+    hipLaunchKernelGGL(fastk::pl_summary, dim3(blocks, B), dim3(fastk::PL_THREADS), 0, stream,
+                       p->wsPart, p->wsC, reinterpret_cast<i64*>(out_stage_weight),
+                       reinterpret_cast<i64*>(out_scaleup_bytes), p->S, p->max_stages);
+    if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
+    return FAST_OK;
+}
+
+int fast_pipeline_time_batched(fast_plan_t* p, int B, const int64_t* stage_weight,
+                               const int64_t* scaleup_bytes, const int32_t* num_stages,
                                const int32_t* stage_order, const int64_t* redis_bytes,
                                double* out_pipeline_time, hipStream_t stream) {
     if (!p || B < 0) return FAST_ERR_INVALID_ARG;
     if (B == 0) return FAST_OK;
-    if (!num_stages || !out_pipeline_time) return FAST_ERR_INVALID_ARG;
-    if (B != p->last_B) return FAST_ERR_INVALID_ARG;    // no synthesis call of this size to evaluate
-    hipLaunchKernelGGL(fastk::pl_time, dim3(B), dim3(fastk::PL_THREADS), 0, stream, p->wsPart,
-                       p->wsC, num_stages, stage_order, reinterpret_cast<const i64*>(redis_bytes),
-                       out_pipeline_time, p->S, p->G, p->max_stages, p->bw_up, p->bw_out, p->delay);
+    if (!stage_weight || !scaleup_bytes || !num_stages || !out_pipeline_time)
+        return FAST_ERR_INVALID_ARG;
+    if (const int rc = check_device(p); rc != FAST_OK) return rc;
+    hipLaunchKernelGGL(fastk::pl_time, dim3(B), dim3(fastk::PL_THREADS), 0, stream,
+                       reinterpret_cast<const i64*>(stage_weight),
+                       reinterpret_cast<const i64*>(scaleup_bytes), num_stages, stage_order,
+                       reinterpret_cast<const i64*>(redis_bytes), out_pipeline_time, p->G,
+                       p->max_stages, p->bw_up, p->bw_out, p->delay);
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     return FAST_OK;
 }

@@ -31,7 +31,7 @@ so_weights(const i64* __restrict__ stage_bytes, const int32_t* __restrict__ num_
     const int s = blockIdx.x * (SO_W_THREADS / 64) + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (s >= P) return;
-    const int K = num_stages[b];
+    const int K = min(num_stages[b], max_stages);     // a count beyond the capacity is not trusted
     u64 key = ~0ull;
     if (s < K) {
         const i64* row = stage_bytes + ((size_t)b * max_stages + s) * S;
@@ -67,7 +67,7 @@ so_sort(u64* __restrict__ keys, int32_t* __restrict__ idx, const int32_t* __rest
     __shared__ int32_t li[SO_CHUNK];
     const int b = blockIdx.x;
     const int tid = threadIdx.x;
-    const int K = num_stages[b];
+    const int K = min(num_stages[b], max_stages);     // a count beyond the capacity is not trusted
     if (K <= 0) return;
     u64* k = keys + (size_t)b * P;
     int32_t* x = idx + (size_t)b * P;

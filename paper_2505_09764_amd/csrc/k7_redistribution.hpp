@@ -73,7 +73,7 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
     const int b = blockIdx.y;
     const int lane = threadIdx.x;
     const int a = blockIdx.x * RD_ROWS + lane;
-    const int K = num_stages[b];
+    const int K = min(num_stages[b], max_stages);     // a count beyond the capacity is not trusted
     if (K <= 0) return;
     i64* sent = reinterpret_cast<i64*>(rd_smem);                    // [d][lane]
     int32_t* next = reinterpret_cast<int32_t*>(sent + (size_t)RD_ROWS * S);   // [d][lane]
@@ -409,7 +409,7 @@ rd_matrices(const i64* __restrict__ traffic, const i64* __restrict__ X,
     const int b = sel[2 * q];
     const int s = sel[2 * q + 1];
     if (b < 0 || b >= B) return;
-    if (s < 0 || s >= num_stages[b]) return;
+    if (s < 0 || s >= min(num_stages[b], max_stages)) return;
     const size_t row = ((size_t)b * max_stages + s) * S + a;
     const int d = stages[row];
     if (d < 0 || d >= S || d == a) return;

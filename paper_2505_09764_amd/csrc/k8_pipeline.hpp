@@ -14,8 +14,8 @@
 //   (A1, C1, D1) then (A2, C2, D2) = (A1 + A2, max(A1 + C2, C1 + D2), D1 + D2).
 // So the K dependent steps become a reduction: every thread composes a contiguous
 // run of stages, thread 0 composes the 256 partial maps in order.  One workgroup
-// per matrix; reads the stage weights and per-server records that the synthesis
-// call left in the plan's workspace.
+// per matrix; the stage weights and the two scale-up volumes of a matrix come from the
+// caller's summary buffers (pl_summary copies them out of the plan's workspace).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -26,21 +26,20 @@ namespace fastk {
 
 constexpr int PL_THREADS = 256;
 
+// grid (ceil(max_stages / 256) + 1, B): the stage weights of matrix b, copied as they are
+// (entries >= K hold whatever an earlier call left), and, by the last block of the row, the
+// largest balancing and intra-server volumes over the servers' records.
 __global__ void __launch_bounds__(PL_THREADS)
-pl_time(const i64* __restrict__ wsPart, const i64* __restrict__ wsC,
-        const int32_t* __restrict__ num_stages, const int32_t* __restrict__ order,
-        const i64* __restrict__ redis, double* __restrict__ out_time, int S, int G, int max_stages,
-        double bw_up, double bw_out, double delay) {
-    __shared__ double sA[PL_THREADS], sC[PL_THREADS], sD[PL_THREADS];
-    __shared__ i64 sBal[PL_THREADS / 64], sIntra[PL_THREADS / 64];
-    const int b = blockIdx.x;
+pl_summary(const i64* __restrict__ wsPart, const i64* __restrict__ wsC, i64* __restrict__ out_weight,
+           i64* __restrict__ out_volume, int S, int max_stages) {
+    const int b = blockIdx.y;
     const int tid = threadIdx.x;
-    const int K = num_stages[b];
-    double* out = out_time + (size_t)b * 2;
-    if (K < 0) {
-        if (tid < 2) out[tid] = 0.0;
+    if (blockIdx.x + 1 < gridDim.x) {
+        const int s = blockIdx.x * PL_THREADS + tid;
+        if (s < max_stages) out_weight[(size_t)b * max_stages + s] = wsC[(size_t)b * max_stages + s];
         return;
     }
+    __shared__ i64 sBal[PL_THREADS / 64], sIntra[PL_THREADS / 64];
     i64 bal = 0, intra = 0;
     for (int a = tid; a < S; a += PL_THREADS) {
         const i64* part = wsPart + ((size_t)b * S + a) * K1_PART;
@@ -53,8 +52,34 @@ pl_time(const i64* __restrict__ wsPart, const i64* __restrict__ wsC,
         intra = max(intra, __shfl_xor(intra, o, 64));
     }
     if ((tid & 63) == 0) { sBal[tid >> 6] = bal; sIntra[tid >> 6] = intra; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < PL_THREADS / 64; ++w) {
+            bal = max(bal, sBal[w]);
+            intra = max(intra, sIntra[w]);
+        }
+        out_volume[(size_t)b * 2] = bal;
+        out_volume[(size_t)b * 2 + 1] = intra;
+    }
+}
 
-    const i64* c = wsC + (size_t)b * max_stages;
+__global__ void __launch_bounds__(PL_THREADS)
+pl_time(const i64* __restrict__ weight, const i64* __restrict__ volume,
+        const int32_t* __restrict__ num_stages, const int32_t* __restrict__ order,
+        const i64* __restrict__ redis, double* __restrict__ out_time, int G, int max_stages,
+        double bw_up, double bw_out, double delay) {
+    __shared__ double sA[PL_THREADS], sC[PL_THREADS], sD[PL_THREADS];
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int K = min(num_stages[b], max_stages);     // a count beyond the capacity is not trusted
+    double* out = out_time + (size_t)b * 2;
+    if (K < 0) {
+        if (tid < 2) out[tid] = 0.0;
+        return;
+    }
+    const i64 bal = volume[(size_t)b * 2], intra = volume[(size_t)b * 2 + 1];
+
+    const i64* c = weight + (size_t)b * max_stages;
     const int32_t* ord = order ? order + (size_t)b * max_stages : nullptr;
     const i64* rb = redis ? redis + (size_t)b * max_stages : nullptr;
     const int per = (K + PL_THREADS - 1) / PL_THREADS;
@@ -79,10 +104,6 @@ pl_time(const i64* __restrict__ wsPart, const i64* __restrict__ wsC,
     sD[tid] = D;
     __syncthreads();
     if (tid == 0) {
-        for (int w = 1; w < PL_THREADS / 64; ++w) {
-            bal = max(bal, sBal[w]);
-            intra = max(intra, sIntra[w]);
-        }
         double tA = 0.0, tC = -INFINITY, tD = 0.0;
         for (int t = 0; t < PL_THREADS; ++t) {
             const double a2 = sA[t], c2 = sC[t], d2 = sD[t];

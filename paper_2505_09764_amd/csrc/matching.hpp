@@ -78,17 +78,23 @@ __device__ __forceinline__ u64 wave_max_u64(u64 x) {
     const u32 lo = hi == mhi ? (u32)x : 0u;
     return ((u64)mhi << 32) | wave_max_u32(lo);
 }
-// v[lane] = val for one lane; val and lane are wave-uniform
+// v[lane] = val for one lane; val and lane are wave-uniform.  gfx950 lets v_writelane read one
+// scalar register besides m0, so the lane index travels in m0; m0 is on the clobber list (the
+// compiler reloads it before its own uses) and clang's warning that it is a reserved register,
+// which it prints for any such clobber, is switched off for these two statements.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void wrlane(u32& v, u32 val, int lane) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0"
-                 : "+v"(v) : "s"(val), "s"(lane));
+                 : "+v"(v) : "s"(val), "s"(lane) : "m0");
 }
 __device__ __forceinline__ void wrlane64(u64& v, u64 val, int lane) {
     u32 lo = (u32)v, hi = (u32)(v >> 32);
     asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\tv_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
-                 : "+v"(lo), "+v"(hi) : "s"((u32)val), "s"((u32)(val >> 32)), "s"(lane));
+                 : "+v"(lo), "+v"(hi) : "s"((u32)val), "s"((u32)(val >> 32)), "s"(lane) : "m0");
     v = ((u64)hi << 32) | lo;
 }
+#pragma clang diagnostic pop
 __device__ __forceinline__ i64 wave_max_i64(i64 v) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {

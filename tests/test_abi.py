@@ -70,7 +70,8 @@ def test_argument_checks_without_device(fastlib):
                                                None, None) == E
     assert fastlib.fast_redistribution_matrices(None, 1, None, None, None, None, None, None, 1, None,
                                                 None, None) == E
-    assert fastlib.fast_pipeline_time_batched(None, 1, None, None, None, None, None) == E
+    assert fastlib.fast_pipeline_time_batched(None, 1, None, None, None, None, None, None, None) == E
+    assert fastlib.fast_plan_summary_batched(None, 1, None, None, None) == E
     fastlib.fast_plan_destroy(None)        # no-op
 
 

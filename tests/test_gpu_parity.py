@@ -542,6 +542,22 @@ def test_error_codes_with_a_plan(torch_cuda):
     assert L.fast_redistribution_matrices(P, 2, ptr(t), ptr(t), ptr(t), ptr(t), ptr(t), ptr(t), 0,
                                           None, None, None) == b.FAST_OK          # nothing selected
     assert L.fast_plan_kernel_ms(P, 0, (b.ctypes.c_float * 3)()) == b.FAST_ERR_INVALID_ARG  # nothing timed
+    # more matrices than one launch grid takes: FAST_ERR_UNSUPPORTED from every batched call
+    big = b.FAST_MAX_BATCH + 1
+    assert L.fast_spreadout_batched(P, big, ptr(t), ptr(sp), None) == b.FAST_ERR_UNSUPPORTED
+    assert L.fast_stage_order_batched(P, big, ptr(out.stage_bytes), ptr(out.num_stages),
+                                      ptr(out.stages), None) == b.FAST_ERR_UNSUPPORTED
+    assert L.fast_stage_offsets_batched(P, big, ptr(out.stages), ptr(out.stage_bytes),
+                                        ptr(out.num_stages), None, ptr(out.stage_bytes),
+                                        None) == b.FAST_ERR_UNSUPPORTED
+    assert L.fast_build_traffic_batched(P, big, 4, ptr(t), ptr(t), 1, ptr(t), ptr(t), None) == \
+        b.FAST_ERR_UNSUPPORTED
+    # the summary describes a synthesis call: none has been made on this plan yet
+    assert L.fast_plan_summary_batched(P, 2, ptr(t), ptr(t), None) == b.FAST_ERR_INVALID_ARG
+    assert L.fast_pipeline_time_batched(P, 2, None, ptr(t), ptr(out.num_stages), None, None, ptr(sp),
+                                        None) == b.FAST_ERR_INVALID_ARG
+    assert L.fast_pipeline_time_batched(P, 2, ptr(t), None, ptr(out.num_stages), None, None, ptr(sp),
+                                        None) == b.FAST_ERR_INVALID_ARG
     # the plan still works after all of that
     syn.synthesize(t, out)
     torch.cuda.synchronize()

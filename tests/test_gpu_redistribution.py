@@ -73,7 +73,9 @@ def _check(oracle, torch, S, G, bw_up, bw_out, t_host, delay=0.0, all_matrices=T
         pipe_worst = syn.pipeline_time(out, o_dev)
         pipe_exact = syn.pipeline_time(out, o_dev, rb)
         torch.cuda.synchronize()
-        assert torch.equal(off, off_only)
+        for b in range(B):                  # rows >= K are left untouched by both calls
+            K = max(int(Ks[b]), 0)
+            assert torch.equal(off[b, :K], off_only[b, :K])
         off_h, rb_h, mats_h = off.cpu().numpy(), rb.cpu().numpy(), mats.cpu().numpy()
         st_h, by_h = out.stages.cpu().numpy(), out.stage_bytes.cpu().numpy()
         ord_h = order.cpu().numpy()
@@ -149,18 +151,40 @@ def test_config5(oracle, torch_cuda):
     _check(oracle, torch_cuda, w.S, w.G, w.bw_up, w.bw_out, t, all_matrices=False, sel_per=4, seed=5)
 
 
-def test_pipeline_needs_a_matching_synthesis_call(torch_cuda):
+def test_pipeline_time_is_given_its_plans_explicitly(oracle, torch_cuda):
+    """fast_pipeline_time_batched evaluates the summary buffers it is handed, not whatever the
+    plan synthesised last; fast_plan_summary_batched describes the latest synthesis call only."""
+    from paper_2505_09764_amd import binding as b
     from paper_2505_09764_amd.binding import Synthesizer, FastError
     torch = torch_cuda
-    syn = Synthesizer(2, 2, 1.0, 1.0)
-    t = torch.ones((3, 4, 4), dtype=torch.int64, device="cuda:0")
+    S, G = 3, 2
+    rng = np.random.default_rng(8)
+    tx = _random_traffic(rng, 3, S, G, "heavy")
+    ty = _random_traffic(rng, 3, S, G, "small")
+    syn = Synthesizer(S, G, 7.0, 2.0)
     out = syn.alloc_outputs(3)
-    with pytest.raises(FastError):
+    with pytest.raises(ValueError):
         syn.pipeline_time(out)              # nothing synthesised yet
-    syn.synthesize(t, out)
-    assert syn.pipeline_time(out).shape == (3, 2)
-    out2 = syn.alloc_outputs(2)
-    with pytest.raises(FastError):
-        syn.pipeline_time(out2)             # batch size differs from the last synthesis call
+    w = torch.empty((3, syn.max_stages), dtype=torch.int64, device="cuda:0")
+    v = torch.empty((3, 2), dtype=torch.int64, device="cuda:0")
+    with pytest.raises(FastError) as e:     # the same through the raw call
+        b.fast_plan_summary_batched(syn.plan, 3, w.data_ptr(), v.data_ptr(), 0)
+    assert e.value.code == b.FAST_ERR_INVALID_ARG
+    outx = syn.synthesize(torch.from_numpy(tx).cuda())
+    syn.summary(outx)
+    outy = syn.synthesize(torch.from_numpy(ty).cuda())      # same batch size, other plans
+    px = syn.pipeline_time(outx).cpu().numpy()               # still X's: its summary was taken
+    py = syn.pipeline_time(outy).cpu().numpy()
+    for t_host, o, got in ((tx, outx, px), (ty, outy, py)):
+        Ks = o.num_stages.cpu().numpy()
+        by = o.stage_bytes.cpu().numpy()
+        for m in range(3):
+            want = oracle.pipeline_time(S, G, 7.0, 2.0, t_host[m], by[m, :Ks[m]])
+            np.testing.assert_allclose(got[m], want, rtol=1e-9, atol=0.0)
+    stale = syn.alloc_outputs(3)
+    with pytest.raises(ValueError):
+        syn.pipeline_time(stale)            # not the batch of the latest synthesis call
+    with pytest.raises(FastError):          # batch size differs from the last synthesis call
+        b.fast_plan_summary_batched(syn.plan, 2, w.data_ptr(), v.data_ptr(), 0)
     torch.cuda.synchronize()
     syn.close()
