@@ -129,6 +129,29 @@ int fast_synthesize_batched(fast_plan_t *plan, int B,
                             hipStream_t stream);
 
 /*
+ * fast_synthesize_batched for callers that cannot allocate device memory: code under HIP graph
+ * capture, serving loops, harnesses that forbid hipMalloc.  Same arguments, same outputs, same
+ * kernels; the workspace is a fixed array of FAST_NOALLOC_SCRATCH_BYTES in the library's device
+ * image instead of the plan's grown-on-demand allocation, and the call makes no hipMalloc,
+ * hipFree or any other allocating call (it records no timing events either:
+ * fast_plan_set_timing does not apply to it).  Limit: B * (24 * S * S + 32 * S) bytes must fit
+ * the array (B <= 84 at 128 servers, <= 5400 at 16), otherwise FAST_ERR_UNSUPPORTED and nothing
+ * is enqueued.  Every call on a GPU, from any plan, uses that GPU's one array: calls that may
+ * overlap on one GPU (different streams, different plans, different threads) race; order them.
+ * The array keeps the last call's contents; nothing in it needs clearing between calls.
+ * fast_plan_summary_batched keeps describing the last fast_synthesize_batched call, not this one.
+ */
+#define FAST_NOALLOC_SCRATCH_BYTES (32 * 1024 * 1024)
+int fast_synthesize_batched_noalloc(fast_plan_t *plan, int B,
+                                    const int64_t *traffic,
+                                    int64_t *out_rebalance,
+                                    int32_t *out_stages,
+                                    int64_t *out_stage_bytes,
+                                    int32_t *out_num_stages,
+                                    double *out_predicted_time,
+                                    hipStream_t stream);
+
+/*
  * Link wake-up delay of the completion-time model (Section 5.4: every transfer step
  * costs a fixed wake-up delay plus size / bandwidth).  `seconds` >= 0 is added to T_pred
  * once per executed step - the balance (if anything is handed off), the intra-server

@@ -24,6 +24,7 @@ FAST_STATUS_STAGE_OVERFLOW = -2
 FAST_STATUS_INTERNAL = -3
 
 EXPORTS = ("fast_plan_create", "fast_plan_max_stages", "fast_synthesize_batched",
+           "fast_synthesize_batched_noalloc",
            "fast_plan_set_wakeup_delay", "fast_plan_set_matching", "fast_spreadout_batched", "fast_build_traffic_batched",
            "fast_stage_order_batched", "fast_stage_offsets_batched",
            "fast_redistribution_batched", "fast_redistribution_matrices",
@@ -57,6 +58,8 @@ def lib():
         L.fast_plan_max_stages.restype = ctypes.c_int
         L.fast_synthesize_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp]
         L.fast_synthesize_batched.restype = ctypes.c_int
+        L.fast_synthesize_batched_noalloc.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp]
+        L.fast_synthesize_batched_noalloc.restype = ctypes.c_int
         L.fast_plan_set_wakeup_delay.argtypes = [vp, ctypes.c_double]
         L.fast_plan_set_wakeup_delay.restype = ctypes.c_int
         L.fast_plan_set_matching.argtypes = [vp, ctypes.c_int]
@@ -113,6 +116,19 @@ def fast_synthesize_batched(plan, B, traffic, out_rebalance, out_stages, out_sta
                                        out_stage_bytes, out_num_stages, out_predicted_time, stream)
     if rc != FAST_OK:
         raise FastError("fast_synthesize_batched", rc)
+
+
+FAST_NOALLOC_SCRATCH_BYTES = 32 * 1024 * 1024
+
+
+def fast_synthesize_batched_noalloc(plan, B, traffic, out_rebalance, out_stages, out_stage_bytes,
+                                    out_num_stages, out_predicted_time, stream):
+    """Raw call: every buffer argument is a device address (int), stream a hipStream_t (int)."""
+    rc = lib().fast_synthesize_batched_noalloc(plan, int(B), traffic, out_rebalance, out_stages,
+                                               out_stage_bytes, out_num_stages,
+                                               out_predicted_time, stream)
+    if rc != FAST_OK:
+        raise FastError("fast_synthesize_batched_noalloc", rc)
 
 
 def fast_plan_set_wakeup_delay(plan, seconds):

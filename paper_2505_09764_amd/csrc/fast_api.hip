@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <mutex>
 #include <new>
 
 #include "k1_rebalance.hpp"
@@ -18,6 +19,12 @@
 #include "k8_pipeline.hpp"
 
 using fastk::i64;
+
+// Workspace of fast_synthesize_batched_noalloc: every GPU the library runs on holds its own
+// copy of this array, at its own address, until the process ends.  Host code never uses the
+// array's name as an address: scratch_address() asks the runtime for the device address once
+// per device and everything else goes through that pointer.
+static __device__ __align__(256) unsigned char scratch[FAST_NOALLOC_SCRATCH_BYTES];
 
 struct fast_plan {
     int S, G;
@@ -48,6 +55,7 @@ struct fast_plan {
     fastk::i64x2* rdList;  // [B][S][max_stages + 1] (bytes per lane, stage) per (stage, source) that sends,
                            //                    grouped by destination, in execution order
     int last_B;            // B of the most recent synthesis call (0 = none)
+    unsigned char* scratch_ptr;   // device address of `scratch` on the plan's device
     // timing: four events per recorded call
     int timing;
     int n_timed;
@@ -174,6 +182,28 @@ rd_offsets_fn rd_offsets_kernel(int S, bool lists, bool ordered) {
     return all ? &fastk::rd_offsets<false, false, true> : &fastk::rd_offsets<false, false, false>;
 }
 
+// Device address of `scratch` on device `dev`, which has to be the current device; looked up
+// once per device.
+constexpr int SCRATCH_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[SCRATCH_MAX_DEVICES];
+
+int scratch_address(int dev, unsigned char** out) {
+    if (dev < 0 || dev >= SCRATCH_MAX_DEVICES) return FAST_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        unsigned char* ptr = nullptr;
+        if (hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)) != hipSuccess ||
+            !ptr) {
+            (void)hipGetLastError();
+            return FAST_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return FAST_OK;
+}
+
 // FAST_OK if the plan's device is the current one (the kernels would otherwise be launched
 // on another GPU than the one that holds the workspace), else the error to return.
 int check_device(const fast_plan* p) {
@@ -278,10 +308,15 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     p->rdStart = p->rdCnt = nullptr;
     p->rdList = nullptr;
     p->last_B = 0;
+    p->scratch_ptr = nullptr;
     p->timing = 0;
     p->n_timed = 0;
     p->ev = nullptr;
 
+    if (const int rc = scratch_address(dev, &p->scratch_ptr); rc != FAST_OK) {
+        delete p;
+        return rc;
+    }
     hipError_t e = fastk::decompose_prepare(S);
     if (e == hipSuccess && link_bw_up < (double)(G - 1) * link_bw_out)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::k3_cost),
@@ -337,6 +372,32 @@ int fast_synthesize_batched(fast_plan_t* p, int B, const int64_t* traffic, int64
     if (ev) ++p->n_timed;
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     p->last_B = B;
+    return FAST_OK;
+}
+
+int fast_synthesize_batched_noalloc(fast_plan_t* p, int B, const int64_t* traffic,
+                                    int64_t* out_rebalance, int32_t* out_stages,
+                                    int64_t* out_stage_bytes, int32_t* out_num_stages,
+                                    double* out_predicted_time, hipStream_t stream) {
+    if (!p || B < 0) return FAST_ERR_INVALID_ARG;
+    if (B == 0) return FAST_OK;
+    if (!traffic || !out_rebalance || !out_stages || !out_stage_bytes || !out_num_stages ||
+        !out_predicted_time)
+        return FAST_ERR_INVALID_ARG;
+    if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
+    if (const int rc = check_device(p); rc != FAST_OK) return rc;
+    // the same four arrays as the plan's workspace, carved out of the static array; every one
+    // of them is written in full by the kernels before it is read, so nothing has to be cleared
+    const size_t S = p->S;
+    const size_t nT = (size_t)B * S * S, nPart = (size_t)B * S * fastk::K1_PART,
+                 nC = (size_t)B * p->max_stages;
+    if ((2 * nT + nPart + nC) * sizeof(i64) > (size_t)FAST_NOALLOC_SCRATCH_BYTES)
+        return FAST_ERR_UNSUPPORTED;
+    i64* base = reinterpret_cast<i64*>(p->scratch_ptr);
+    const synth_workspace ws = {base, base + nT, base + 2 * nT, base + 2 * nT + nPart};
+    enqueue_synthesis(p, ws, B, traffic, out_rebalance, out_stages, out_stage_bytes, out_num_stages,
+                      out_predicted_time, nullptr, stream);
+    if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     return FAST_OK;
 }
 

@@ -55,6 +55,8 @@ def test_argument_checks_without_device(fastlib):
     assert fastlib.fast_plan_max_stages(None) == -1
     assert fastlib.fast_synthesize_batched(None, 1, None, None, None, None, None, None, None) == \
         b.FAST_ERR_INVALID_ARG
+    assert fastlib.fast_synthesize_batched_noalloc(None, 1, None, None, None, None, None, None,
+                                                   None) == b.FAST_ERR_INVALID_ARG
     assert fastlib.fast_plan_set_timing(None, 1) == b.FAST_ERR_INVALID_ARG
     assert fastlib.fast_plan_timed_calls(None) == -1
     assert fastlib.fast_plan_kernel_ms(None, 0, None) == b.FAST_ERR_INVALID_ARG
