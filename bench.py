@@ -22,6 +22,8 @@ quoted on.  Prints ONE JSON line:
                  B = 64 occupies a quarter of the compute units by construction
   fewer_stages_variant  the same batch with a bottleneck assignment per stage
                       (fast_plan_set_matching): stage count and time of its decomposition kernel
+  all_configs    the other four benchmark configurations at their own batch sizes, 20 timed
+                 calls each: schedules/s, p50/p99 per schedule, per-kernel ms, B = 1 latency
 """
 import argparse
 import json
@@ -68,12 +70,24 @@ def time_steps(torch, syn, traffic, out, steps, warmup, per_kernel):
     return total_ms, step_ms, kms, wall
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(w, host_traffic, n_all, n_single):
     """Oracle as it stands on this machine's host cores: all-core throughput with one
-    matrix per task, and single-thread time per schedule."""
+    matrix per task, and single-thread time per schedule.  The pool is the machine's CPU share
+    (16 threads for one GPU), whatever the host reports."""
     from oracle import oracle as O
     O.lib()
-    cores = min(os.cpu_count() or 1, 16)
+    host_cpus = os.cpu_count() or 1
+    cores = min(host_cpus, 16)
     n_all = min(n_all, host_traffic.shape[0])
     n_single = min(n_single, host_traffic.shape[0])
 
@@ -93,7 +107,33 @@ def cpu_baseline(w, host_traffic, n_all, n_single):
         "sample": f"first {n_all} matrices of the batch, one matrix per task on {threads} "
                   f"threads; single-thread time from the first {n_single}",
         "single_thread_us_per_schedule_p50": percentile(single, 0.5) * 1e6,
+        "host_cpus": host_cpus, "cpu_model": cpu_model(),
     }
+
+
+def small_config(torch, binding, W, ci, steps, warmup, dev):
+    """One of the other benchmark configurations at its own batch size: throughput, per-schedule
+    time, per-kernel time and single-matrix latency (not part of `value`)."""
+    w = W.config(ci)
+    traffic = W.generate_device(w, w.B, dev)
+    syn = binding.Synthesizer(w.S, w.G, w.bw_up, w.bw_out, dev)
+    out = syn.alloc_outputs(w.B)
+    total_ms, step_ms, kms, _ = time_steps(torch, syn, traffic, out, steps, warmup, True)
+    K = out.num_stages.cpu().numpy()
+    assert (K >= 0).all(), "a matrix failed to synthesise"
+    per = [m * 1e3 / w.B for m in step_ms]
+    syn1 = binding.Synthesizer(w.S, w.G, w.bw_up, w.bw_out, dev)
+    t1 = traffic[-1:].contiguous()
+    out1 = syn1.alloc_outputs(1)
+    _, s1, _, _ = time_steps(torch, syn1, t1, out1, steps, warmup, False)
+    syn1.close()
+    syn.close()
+    return {"workload": w.name, "B": w.B, "schedules_per_s": w.B * steps / (total_ms * 1e-3),
+            "ms_per_step": total_ms / steps, "p50_us_per_schedule": percentile(per, 0.5),
+            "p99_us_per_schedule": percentile(per, 0.99),
+            "stages_per_schedule_mean": float(K.mean()),
+            "kernels_ms": [sum(k[i] for k in kms) / len(kms) for i in range(3)],
+            "latency_b1_p50_us": percentile(s1, 0.5) * 1e3}
 
 
 def main():
@@ -104,6 +144,8 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size B")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-all-configs", action="store_true",
+                    help="skip the short runs of the other benchmark configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of 512 MiB (read 512 MiB + write "
                          "512 MiB) so a counter profile of this run contains a kernel of known "
@@ -252,8 +294,16 @@ def main():
 
     cpu = None
     if not args.no_cpu:
-        host = traffic[:32].cpu().numpy()
-        cpu = cpu_baseline(w, host, n_all=32 if S >= 64 else 256, n_single=4 if S >= 64 else 32)
+        n_all = min(B, 64 if S >= 64 else 256)
+        host = traffic[:n_all].cpu().numpy()
+        cpu = cpu_baseline(w, host, n_all=n_all, n_single=min(B, 16))
+
+    # The other benchmark configurations at their own batch sizes (outside the timed region of
+    # `value`; small: cfg1-cfg4 take a few seconds together)
+    others = None
+    if args.batch is None and not args.no_all_configs:
+        others = [small_config(torch, binding, W, ci, 20, 3, dev) for ci in (1, 2, 3, 4)
+                  if ci != args.config]
 
     stages_total = int(K.sum())
     result = {
@@ -284,12 +334,22 @@ def main():
                        "achieved_GBs": k2_bytes / (k_avg[1] * 1e-3) / 1e9,
                        "algorithmic_bytes": k2_bytes},
         "end_to_end_GBs": (k1_bytes + k2_bytes + k3_bytes) / (ms_per_step * 1e-3) / 1e9,
+        "end_to_end_frac_of_hbm_peak":
+            (k1_bytes + k2_bytes + k3_bytes) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        # the three targets the benchmark spec names, as measured by this run
+        "targets": {
+            "streaming_kernel_at_least_40pct_of_hbm_peak": bool(k1_gbs / HBM_PEAK_GBS >= 0.40),
+            "batch_amortised_p50_under_1ms_per_schedule": bool(percentile(per_sched_us, 0.5) < 1000.0),
+            "single_matrix_latency_under_1ms": (bool(lat["p50_us"] < 1000.0) if lat else
+                                                bool(B == 1 and ms_per_step < 1.0)),
+        },
         "latency_b1": lat,
         "spreadout_baseline": spo,
         "pipeline_analysis": pipe,
         "full_chip": full,
         "fewer_stages_variant": fewer,
         "cpu_baseline": cpu,
+        "all_configs": others,
     }
     syn.close()
     print(json.dumps(result))

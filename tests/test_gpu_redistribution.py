@@ -142,12 +142,12 @@ def test_configs(oracle, torch_cuda, ci, B):
 
 
 def test_config5(oracle, torch_cuda):
-    """Full size (128 x 8): two matrices, sampled stages for the matrices, every stage for the
-    offsets and volumes."""
+    """Full size (128 x 8): eight matrices, every stage for the offsets and volumes, sampled
+    stages for the redistribution matrices."""
     from paper_2505_09764_amd import workloads as W
     w = W.config(5)
-    say(f"[redis] {w.name} B=2")
-    t = W.generate_device(w, 2).cpu().numpy()
+    say(f"[redis] {w.name} B=8")
+    t = W.generate_device(w, 8).cpu().numpy()
     _check(oracle, torch_cuda, w.S, w.G, w.bw_up, w.bw_out, t, all_matrices=False, sel_per=4, seed=5)
 
 
