@@ -5,24 +5,35 @@
 // chain of dependent steps - find a perfect matching, take the smallest matched
 // entry as the stage weight, subtract, repair the matching - and a generic
 // matrix needs about (S-1)^2 stages, so the design goal is the fewest
-// instructions on the dependent path of one stage, not memory throughput (one
-// wavefront issues an instruction every 5 to 8 cycles whatever its kind):
+// instructions per stage, not memory throughput: a lone wavefront issues one
+// instruction every four cycles at best, whatever its kind, and waits out every
+// dependency on top of that.
 //   * a single wavefront owns the matrix, so no step needs a workgroup barrier;
 //     lane l owns rows l, l+64 and columns l, l+64 (S <= 128);
-//   * the residual matrix R = Q + A lives in LDS (S*S int64) and is only touched
-//     when the matching changes: the residual of each row's matched cell is held
-//     in a register and written back when the row is re-matched;
-//   * the support of R is kept as one S-bit row mask per column in registers;
+//   * the residual matrix R = Q + A lives in LDS (int64 words, odd row stride so
+//     that a column - one cell per lane - spreads over the banks).  The residual of
+//     each row's matched cell is also held in a register; after every subtraction
+//     the register is written back, so LDS is current for every cell;
+//   * almost every stage exhausts exactly one cell (r0, f).  The canonical search
+//     then looks, on its second level, for the lowest row a1 that has a positive
+//     cell in the unmatched column f and whose own column d1 has a positive cell
+//     in row r0.  Both conditions are reads of R: every lane reads R[its row][f]
+//     and R[r0][its column], a ballot of "both positive" gives the candidate rows,
+//     and the two cells read by a1's lane are exactly the cells that get matched
+//     next (a1 takes (a1, f), r0 takes (r0, d1)), so the repair and the reload of
+//     the two re-matched rows cost one LDS round trip and no bit-mask work;
+//   * the support of R as one S-bit row mask per column is what the deeper
+//     repairs and the general search work on.  It is kept in LDS, where the stage
+//     loop clears one bit per exhausted cell with an LDS atomic that nothing
+//     waits for, and loaded into registers only by the repairs that search:
 //     frontiers, visited sets and the set of unmatched columns are wave-uniform
-//     bit masks, so one breadth-first level is a few AND/compare operations per
-//     lane plus ballots, and "does the frontier reach an unmatched column" is a
-//     scalar test on that column's mask;
-//   * parents are not stored: the parent of a column is recomputed while the
-//     augmenting path is flipped, as the lowest set bit of (its support mask AND
-//     the frontier of the level that reached it);
-//   * almost every stage exhausts exactly one cell (r0, f) and is repaired by a
-//     path of at most three levels; that case runs as straight-line code, every
-//     other case goes through the general search;
+//     bit masks, one breadth-first level is a few AND/compare operations per lane
+//     plus ballots, parents are recomputed while the augmenting path is flipped;
+//   * the stages that end in such a two-level repair run in an inner loop of
+//     their own; everything else (several cells exhausted at once, a repair of
+//     three levels or more, the end) leaves it with a reason.  Keeping the common
+//     case a loop with a single back edge is what keeps the compiler from
+//     shuffling the loop-carried registers at every merge;
 //   * the virtual matrix A of the embedding (Section 4.4 "Adapting an arbitrary
 //     matrix to a valid form") is never stored: pouring row deficits into column
 //     deficits in ascending order makes A[a][d] the overlap of two prefix-sum
@@ -31,12 +42,13 @@
 //     when such a cell gets matched;
 //   * no residual exceeds L, the largest row/column sum, so when L < 2^31 the matrix
 //     is repacked in place to 32-bit words and the stage loop runs on 32-bit
-//     registers; when S fills the lane slots exactly (64 or 128) the stage loop
-//     carries no bounds predicates.  Predicated LDS writes and mid-loop exits cost a
-//     lone wavefront far more than their instruction count suggests (exec-mask
-//     save/restore pairs, scalar branches at 11-13 cycles per instruction), so the
-//     dependent path avoids them: unconditional write-back of the old matched cell,
-//     the stage weight stored by every lane, error exits checked once per stage.
+//     registers; the real bytes left in a cell never exceed the largest entry of
+//     Q, so they are counted in 32 bits whenever that fits, even where virtual
+//     bytes push the residuals beyond 32 bits; when S fills the lane slots exactly
+//     (64 or 128) the stage loop carries no bounds predicates.  Predicated LDS
+//     writes and mid-loop exits cost a lone wavefront far more than their
+//     instruction count suggests, so the stage avoids them: unconditional
+//     write-back, the stage weight stored by every lane.
 //
 // Canonical choices that make the result a function of the matrix alone (the
 // paper leaves them open): level-synchronous search from one unmatched row, the
@@ -60,13 +72,21 @@ namespace fastk {
 
 constexpr int K2_THREADS = 64;
 
-// R[S][S], column deficit intervals PC[S], EC[S], frontier history [(S+2)][2]
+// LDS: R[S][row stride], column deficit intervals PC[S], EC[S], frontier history [(S+2)][2].
+// Row stride of R in words: odd, so that a column of the matrix (one cell per lane, read when
+// a row looks for its cell in the unmatched column) falls into different LDS banks.
+__host__ __device__ inline int k2_row_stride(int S) { return S | 1; }
 __host__ __device__ inline size_t k2_lds_data_bytes(int S) {
-    return (size_t)S * S * 8 + (size_t)2 * S * 8 + (size_t)(S + 2) * 16;
+    return (size_t)S * k2_row_stride(S) * 8 + (size_t)2 * S * 8 + (size_t)(S + 2) * 16;
 }
-// ... plus one spare word per lane slot and one in front: the lane slots that hold no row
-// (S below 64 * NR) read and write there, so the per-stage reload needs no bounds predicate
-inline size_t k2_lds_bytes(int S) { return k2_lds_data_bytes(S) + (size_t)(2 * 64 + 1) * 8; }
+
+// ... plus a spare region that the lane slots without a row (S below 64 * NR) read and write
+// instead of a row of R, so that the stage loop needs no bounds predicate, plus the support
+// masks: one 128-bit row mask per column
+__host__ __device__ inline size_t k2_lds_spare_bytes(int S) { return (size_t)(S + 2) * 8; }
+inline size_t k2_lds_bytes(int S) {
+    return k2_lds_data_bytes(S) + k2_lds_spare_bytes(S) + (size_t)128 * 16;
+}
 
 // NR = rows (and columns) per lane: 1 for S <= 64, 2 for S <= 128.
 // NR: rows and columns per lane; FULL: S == 64 * NR, every lane slot holds a real row (the
@@ -79,12 +99,14 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
           int b, int lane, unsigned char* k2_smem) {
     const int S = FULL ? 64 * NR : S_arg;       // FULL: a compile-time constant
     u64* R = reinterpret_cast<u64*>(k2_smem);
-    i64* PC = reinterpret_cast<i64*>(R + (size_t)S * S);
+    const int RS = k2_row_stride(S);
+    i64* PC = reinterpret_cast<i64*>(R + (size_t)S * RS);
     i64* EC = PC + S;
     u64* Fh = reinterpret_cast<u64*>(EC + S);       // [level][2]
 
     i64 diag[NR], PR[NR], ER[NR];
-    const i64 L = embed_into_lds<NR>(wsQ, wsPart, b, S, lane, R, PC, EC, diag, PR, ER);
+    i64 qmax = 0;
+    const i64 L = embed_into_lds<NR>(wsQ, wsPart, b, S, RS, lane, R, PC, EC, diag, PR, ER, qmax);
     if (L <= 0) {
         if (lane == 0) out_num[b] = (int32_t)L;     // -1: invalid input, 0: nothing to send
         return;
@@ -99,7 +121,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         for (int w = 0; w < NR; ++w) cm[k][w] = 0;
         if (x < S) {
             for (int a = 0; a < S; ++a) {
-                const u64 pos = (R[(size_t)a * S + x] & ~VFLAG) != 0;
+                const u64 pos = (R[a * RS + x] & ~VFLAG) != 0;
 #pragma unroll
                 for (int w = 0; w < NR; ++w)
                     if ((a >> 6) == w) cm[k][w] |= pos << (a & 63);
@@ -111,10 +133,12 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     // residual matrix is repacked in place (flag in bit 31) and every per-stage subtraction,
     // comparison and select is one instruction instead of two.
     const bool narrow = L < ((i64)1 << 31);
-    if (narrow) repack_narrow(R, S, lane);
-    auto run = [&](auto tag) {
+    if (narrow) repack_narrow(R, S * RS, lane);
+    auto run = [&](auto tag, auto rltag) {
         typedef decltype(tag) V;                // word type of the residuals
         typedef std::make_signed_t<V> SV;
+        typedef decltype(rltag) RL;             // signed type of the real bytes left in a cell
+        constexpr i64 RL_MAX = (i64)std::numeric_limits<RL>::max();
         constexpr V VF = (V)((V)1 << (sizeof(V) * 8 - 1));   // the cell holds virtual bytes
         V* Rv = reinterpret_cast<V*>(k2_smem);
         auto wave_min = [&](V v) -> V {
@@ -128,12 +152,21 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             lid[k] = lane + 64 * k;
             // a slot without a row keeps mr = loaded = -1: base + (-1) is its spare word
             // (the first reload, before any row is loaded, reads base + 0: the next spare word)
-            const u32 spare = (u32)(k2_lds_data_bytes(S) / sizeof(V)) + (u32)(lane + 64 * k) + 1u;
-            rowbase[k] = lane + 64 * k < S ? (u32)(lane + 64 * k) * (u32)S : spare;
+            const u32 spare = (u32)(k2_lds_data_bytes(S) / sizeof(V)) + 1u;
+            rowbase[k] = lane + 64 * k < S ? (u32)(lane + 64 * k) * (u32)RS : spare;
         }
         int mr[NR], loaded[NR];
-        SV rv[NR], rl[NR];
-        V vfl[NR];
+        SV rv[NR];
+        RL rl[NR];
+        u32 vfl[NR];       // bit 31: the matched cell holds virtual bytes (the flag of its LDS word)
+        auto with_flag = [&](SV v, u32 fl) -> V {
+            if constexpr (sizeof(V) == 8) return (V)v | ((V)fl << 32);
+            else return (V)v | fl;
+        };
+        auto flag_of = [&](V x) -> u32 {
+            if constexpr (sizeof(V) == 8) return (u32)(x >> 32) & 0x80000000u;
+            else return (u32)x & 0x80000000u;
+        };
 #pragma unroll
         for (int k = 0; k < NR; ++k) {
             mr[k] = -1;
@@ -188,10 +221,10 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             for (int k = 0; k < NR; ++k) {
                 ch[k] = mr[k] != loaded[k];
                 if constexpr (PLAIN) {
-                    Rv[rowbase[k] + (u32)loaded[k]] = (V)rv[k] | vfl[k];
+                    Rv[rowbase[k] + (u32)loaded[k]] = with_flag(rv[k], vfl[k]);
                     x[k] = Rv[rowbase[k] + (u32)mr[k]];
                 } else {
-                    if (ch[k] && rv[k] > 0) Rv[rowbase[k] + (u32)loaded[k]] = (V)rv[k] | vfl[k];
+                    if (ch[k] && rv[k] > 0) Rv[rowbase[k] + (u32)loaded[k]] = with_flag(rv[k], vfl[k]);
                     x[k] = Rv[rowbase[k] + (u32)max(mr[k], 0)];
                 }
             }
@@ -199,9 +232,9 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 #pragma unroll
             for (int k = 0; k < NR; ++k) {
                 const V val = x[k] & (V)~VF;
-                const V fl = x[k] & VF;
+                const u32 fl = flag_of(x[k]);
                 rv[k] = ch[k] ? (SV)val : rv[k];
-                rl[k] = ch[k] ? (SV)val : rl[k];
+                rl[k] = ch[k] ? (RL)val : rl[k];
                 anyv |= ballot(ch[k]) & ballot(fl != 0);
                 vfl[k] = ch[k] ? fl : vfl[k];
                 loaded[k] = mr[k];
@@ -214,7 +247,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                         const i64 l = max(PR[k], PC[d]);
                         const i64 h = min(ER[k], EC[d]);
                         const i64 av = (h > l ? h - l : 0) + (d == lid[k] ? diag[k] : 0);
-                        rl[k] = (i64)rv[k] > av ? (SV)((i64)rv[k] - av) : (SV)0;
+                        rl[k] = (i64)rv[k] > av ? (RL)((i64)rv[k] - av) : (RL)0;
                     }
                 }
             }
@@ -231,6 +264,27 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 #pragma unroll
         for (int k = 0; k < NR; ++k)
             if (lane + 64 * k >= S) rv[k] = std::numeric_limits<SV>::max();     // never the minimum, never zero
+
+        // The support masks also live in LDS, one 128-bit row mask per column: the stage loop
+        // clears bits there (one LDS atomic, nothing waits for it) and only the repairs that
+        // need a search load them back into registers.
+        u64* cmL = reinterpret_cast<u64*>(k2_smem + k2_lds_data_bytes(S) + k2_lds_spare_bytes(S));
+        auto masks_to_lds = [&]() {
+#pragma unroll
+            for (int k = 0; k < NR; ++k)
+#pragma unroll
+                for (int w = 0; w < 2; ++w) cmL[(lane + 64 * k) * 2 + w] = w < NR ? cm[k][w < NR ? w : 0] : 0ull;
+        };
+        auto masks_from_lds = [&]() {
+#pragma unroll
+            for (int k = 0; k < NR; ++k)
+#pragma unroll
+                for (int w = 0; w < NR; ++w) cm[k][w] = cmL[(lane + 64 * k) * 2 + w];
+        };
+        masks_to_lds();
+        u64 LIVE[NR];      // lane slots that hold a row
+#pragma unroll
+        for (int k = 0; k < NR; ++k) LIVE[k] = ballot(lane + 64 * k < S);
 
         int32_t* stg = out_stages + (size_t)b * max_stages * S;
         i64* byt = out_bytes + (size_t)b * max_stages * S;
@@ -274,124 +328,202 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             }
         };
 
+        // cell (a, d) has left the support (a, d wave-uniform): one LDS atomic that nothing waits
+        // for; every lane sends the same AND to the same word (written as an instruction of its
+        // own: the compiler would wrap an atomicAnd into a dozen instructions that pick one lane)
+        auto clear_edge = [&](int a, int d) {
+            const u32 addr = (u32)(k2_lds_data_bytes(S) + k2_lds_spare_bytes(S)) +
+                             (u32)d * 16u + (u32)(a >> 5) * 4u;
+            const u32 keep = ~(1u << (a & 31));
+            asm volatile("ds_and_b32 %0, %1" : : "v"(addr), "v"(keep) : "memory");
+        };
+        // LDS follows every subtraction: each row's matched cell gets its new residual (the
+        // exhausted one its zero), so that R in LDS is current for every cell.  Where it sits in
+        // the stage is a matter of measurement: before the reads of the repair when a lane holds
+        // two rows, after them (with the one stale cell masked out) when it holds one.
+        constexpr bool LATE_WRITE_BACK = NR == 1;
+        auto write_back = [&]() {
+#pragma unroll
+            for (int k = 0; k < NR; ++k) Rv[rowbase[k] + (u32)mr[k]] = with_flag(rv[k], vfl[k]);
+        };
+        enum { GO_ON = 0, DONE, OVERFLOW, GENERAL, DEEP };
         for (;;) {
-            if (__builtin_expect(s >= max_stages, 0)) { status = -2; break; }
-            V mine = (V)rv[0];
-            if constexpr (NR == 2) mine = (V)rv[1] < mine ? (V)rv[1] : mine;
-            const i64 c64 = (i64)wave_min(mine);    // stage weight: wave-uniform, fits SV
-            const SV c = (SV)c64;
+            // ---- the stages that end in a two-level repair run in this inner loop; anything
+            // else leaves it with a reason and is handled below
+            int why = GO_ON;
             u64 Z[NR];
             bool zero[NR];
-#pragma unroll
-            for (int k = 0; k < NR; ++k) {
-                const SV real = c < rl[k] ? c : rl[k];
-                rl[k] -= real;
-                rv[k] -= c;
-                if (FULL || lid[k] < S) {
-                    srow[lid[k]] = real > 0 ? mr[k] : -1;
-                    brow[lid[k]] = (i64)real;
-                }
-                zero[k] = rv[k] == 0;
-                Z[k] = ballot(zero[k]);
-            }
-            cw[s] = c64;      // every lane stores the same word: no divergent branch on the path
-            ++s;
-            srow += S;
-            brow += S;
-            Lrem -= c64;
-            if (__builtin_expect(Lrem == 0, 0)) break;
-
-            int nz = 0;
-#pragma unroll
-            for (int w = 0; w < NR; ++w) nz += __builtin_popcountll(Z[w]);
-            if (__builtin_expect(nz == 1, 1)) {
-                // ---- fast path: one exhausted cell (r0, f); f is the only unmatched column.
-                // Row r0 keeps naming f as its column until the flip; f is not adjacent to
-                // r0 any more, so r0 cannot enter a frontier through it.
-                const int r0 = lowest(Z);
-                const int f = mr_of(r0);
-                const u64 bit0 = 1ull << (r0 & 63);
-                u64 cmf[NR], N1[NR], F2[NR];
-                // KF = column slot of f (compile-time in each branch); the mask word of r0 is handled
-                // by data: clr[w] is bit r0 in its own word and 0 in the other
-                u64 clr[NR];
-#pragma unroll
-                for (int w = 0; w < NR; ++w) clr[w] = (r0 >> 6) == w ? bit0 : 0ull;
-                auto level1 = [&](auto KFc) {
-                    constexpr int KF = decltype(KFc)::value;
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) {
-                        cmf[w] = rdl64(cm[KF][w], f & 63) & ~clr[w];
-                        wrlane64(cm[KF][w], cmf[w], f & 63);
-                    }
-#pragma unroll
-                    for (int k = 0; k < NR; ++k) {
-                        u64 t = 0;
-#pragma unroll
-                        for (int w = 0; w < NR; ++w) t |= cm[k][w] & clr[w];
-                        N1[k] = ballot(t != 0);
-                    }
-                };
-                if constexpr (NR == 2) {
-                    if ((f >> 6) == 0) level1(std::integral_constant<int, 0>{});
-                    else level1(std::integral_constant<int, 1>{});
+            int r0 = 0, f = 0;
+            do {
+                if (__builtin_expect(s >= max_stages, 0)) { why = OVERFLOW; break; }
+                V mine = (V)rv[0];
+                if constexpr (NR == 2) mine = (V)rv[1] < mine ? (V)rv[1] : mine;
+                const i64 c64 = (i64)wave_min(mine);    // stage weight: wave-uniform, fits SV
+                // one copy of the weight in vector registers for all the per-lane arithmetic
+                SV c;
+                if constexpr (sizeof(V) == 8) {
+                    u32 clo, chi;
+                    asm volatile("v_mov_b32 %0, %2\n\tv_mov_b32 %1, %3"
+                                 : "=v"(clo), "=v"(chi) : "s"((u32)c64), "s"((u32)((u64)c64 >> 32)));
+                    c = (SV)(((u64)chi << 32) | clo);
                 } else {
-                    level1(std::integral_constant<int, 0>{});
+                    u32 clo;
+                    asm volatile("v_mov_b32 %0, %1" : "=v"(clo) : "s"((u32)c64));
+                    c = (SV)clo;
                 }
-                // every row is matched here (r0 nominally), so no "unmatched" test is needed
+                RL cr;
+                if constexpr (sizeof(RL) == sizeof(SV)) cr = (RL)c;
+                else cr = (RL)(c64 < RL_MAX ? c64 : RL_MAX);
 #pragma unroll
                 for (int k = 0; k < NR; ++k) {
-                    const int m = mr[k];
-                    u64 t;
-                    if constexpr (NR == 2) t = (m & 64) ? (N1[1] >> (m & 63)) : (N1[0] >> (m & 63));
-                    else t = N1[0] >> (m & 63);
-                    F2[k] = ballot((t & 1) != 0);
+                    const RL real = cr < rl[k] ? cr : rl[k];
+                    rl[k] -= real;
+                    rv[k] -= c;
+                    if (FULL || lid[k] < S) {
+                        srow[(u32)lid[k]] = real > 0 ? mr[k] : -1;
+                        brow[(u32)lid[k]] = (i64)(std::make_unsigned_t<RL>)real;
+                    }
+                    zero[k] = rv[k] == 0;
+                    Z[k] = ballot(zero[k]);
                 }
+                cw[s] = (i64)c;   // every lane stores the same word: no divergent branch on the path
+                ++s;
+                srow += S;
+                brow += S;
+                Lrem -= c64;
+                if (__builtin_expect(Lrem == 0, 0)) { why = DONE; break; }
+                if constexpr (!LATE_WRITE_BACK) write_back();
+                int nz = 0;
+#pragma unroll
+                for (int w = 0; w < NR; ++w) nz += __builtin_popcountll(Z[w]);
+                if (__builtin_expect(nz != 1, 0)) { why = GENERAL; break; }
+                // one exhausted cell (r0, f); f is the only unmatched column.  A two-level repair
+                // takes the lowest row a1 that has a positive cell in column f and whose column
+                // d1 has a positive cell in row r0: both tests are reads of R, and the two cells
+                // read by a1's lane are the ones that get matched.
+                r0 = lowest(Z);
+                f = mr_of(r0);
+                V ea[NR], eb[NR];
+#pragma unroll
+                for (int k = 0; k < NR; ++k) {
+                    ea[k] = Rv[rowbase[k] + (u32)f];
+                    eb[k] = Rv[(u32)r0 * (u32)RS + (u32)(FULL ? mr[k] : max(mr[k], 0))];
+                }
+                if constexpr (LATE_WRITE_BACK) write_back();
+                clear_edge(r0, f);
                 u64 c2[NR];
 #pragma unroll
-                for (int w = 0; w < NR; ++w) c2[w] = cmf[w] & F2[w];
-                if (__builtin_expect(any(c2), 1)) {
-                    const int a1 = lowest(c2);
-                    const int d1 = mr_of(a1);
-                    set_mr(a1, f);
-                    set_mr(r0, d1);
+                for (int k = 0; k < NR; ++k) {
+                    // both cells positive (flag bit aside): fold each to 32 bits, take the smaller
+                    u32 fa, fb;
+                    if constexpr (sizeof(V) == 8) {
+                        fa = ((u32)((u64)ea[k] >> 32) & 0x7FFFFFFFu) | (u32)ea[k];
+                        fb = ((u32)((u64)eb[k] >> 32) & 0x7FFFFFFFu) | (u32)eb[k];
+                    } else {
+                        fa = (u32)ea[k] & 0x7FFFFFFFu;
+                        fb = (u32)eb[k] & 0x7FFFFFFFu;
+                    }
+                    c2[k] = ballot(min(fa, fb) != 0);
+                    if constexpr (LATE_WRITE_BACK)
+                        if ((r0 >> 6) == k) c2[k] &= ~(1ull << (r0 & 63));     // its cell (r0, f) was read stale
+                    if constexpr (!FULL) c2[k] &= LIVE[k];
+                }
+                if (__builtin_expect(!any(c2), 0)) { why = DEEP; break; }
+                const int a1 = lowest(c2);
+                const int d1 = mr_of(a1);
+                V vb;
+                if constexpr (NR == 2) {
+                    if constexpr (sizeof(V) == 8) {
+                        const u64 b0 = rdl64((u64)eb[0], a1 & 63), b1 = rdl64((u64)eb[1], a1 & 63);
+                        vb = (V)((a1 & 64) ? b1 : b0);
+                    } else {
+                        const u32 b0 = rdl((u32)eb[0], a1 & 63), b1 = rdl((u32)eb[1], a1 & 63);
+                        vb = (V)((a1 & 64) ? b1 : b0);
+                    }
                 } else {
-                    bool done = false;
-                    if (any(N1)) {
-                        set_mr(r0, -1);
-                        u64 N2[NR], F3[NR], c3[NR];
-                        expand(F2, N2);
+                    if constexpr (sizeof(V) == 8) vb = (V)rdl64((u64)eb[0], a1);
+                    else vb = (V)rdl((u32)eb[0], a1);
+                }
+                u64 anyv = 0;
 #pragma unroll
-                        for (int w = 0; w < NR; ++w) N2[w] &= ~N1[w];
-                        rows_matched_into(N2, F3);
+                for (int k = 0; k < NR; ++k) {
+                    const bool isA = lid[k] == a1, isR = lid[k] == r0;
+                    const V x = isA ? ea[k] : vb;
+                    const bool ch = isA || isR;
+                    const V val = x & (V)~VF;
+                    const u32 fl = flag_of(x);
+                    rv[k] = ch ? (SV)val : rv[k];
+                    rl[k] = ch ? (RL)val : rl[k];
+                    vfl[k] = ch ? fl : vfl[k];
+                    anyv |= ballot(ch) & ballot((SV)x < 0);
+                    mr[k] = isA ? f : (isR ? d1 : mr[k]);
+                }
+                if (__builtin_expect(anyv != 0, 0)) {
 #pragma unroll
-                        for (int w = 0; w < NR; ++w) c3[w] = cmf[w] & F3[w];
-                        if (any(c3)) {
-                            const int a2 = lowest(c3);
-                            const int d2 = mr_of(a2);
-                            u64 cd[NR];
-                            col_mask(d2, cd);
-#pragma unroll
-                            for (int w = 0; w < NR; ++w) cd[w] &= F2[w];
-                            const int a1 = lowest(cd);
-                            const int d1 = mr_of(a1);
-                            set_mr(a2, f);
-                            set_mr(a1, d2);
-                            set_mr(r0, d1);
-                            done = true;
+                    for (int k = 0; k < NR; ++k) {
+                        if ((lid[k] == a1 || lid[k] == r0) && vfl[k] != 0) {
+                            const int d = mr[k];
+                            const i64 l = max(PR[k], PC[d]);
+                            const i64 h = min(ER[k], EC[d]);
+                            const i64 av = (h > l ? h - l : 0) + (d == lid[k] ? diag[k] : 0);
+                            rl[k] = (i64)rv[k] > av ? (RL)((i64)rv[k] - av) : (RL)0;
                         }
                     }
-                    if (!done) {
-                        // deeper than three levels: let the general search redo it
-                        set_mr(r0, -1);
+                }
+            } while (true);
+            if (why == DONE) break;
+            if (why == OVERFLOW) { status = -2; break; }
 #pragma unroll
-                        for (int w = 0; w < NR; ++w)
-                            if ((f >> 6) == w) FREEC[w] |= 1ull << (f & 63);
-                        if (!augment(r0)) status = -3;     // leaves the loop before the sync
+            for (int k = 0; k < NR; ++k) loaded[k] = mr[k];     // what LDS and the registers describe
+            if (why == DEEP) {
+                // not a two-level repair: level three in straight-line code on the masks,
+                // anything deeper through the general search
+                masks_from_lds();
+                const u64 bit0 = 1ull << (r0 & 63);
+                u64 cmf[NR], N1[NR], F2[NR];
+                col_mask(f, cmf);
+                {
+                    u64 F1[NR];
+#pragma unroll
+                    for (int w = 0; w < NR; ++w) F1[w] = (r0 >> 6) == w ? bit0 : 0ull;
+                    expand(F1, N1);
+                    rows_matched_into(N1, F2);
+                }
+                bool done = false;
+                if (any(N1)) {
+                    set_mr(r0, -1);
+                    u64 N2[NR], F3[NR], c3[NR];
+                    expand(F2, N2);
+#pragma unroll
+                    for (int w = 0; w < NR; ++w) N2[w] &= ~N1[w];
+                    rows_matched_into(N2, F3);
+#pragma unroll
+                    for (int w = 0; w < NR; ++w) c3[w] = cmf[w] & F3[w];
+                    if (any(c3)) {
+                        const int a2 = lowest(c3);
+                        const int d2 = mr_of(a2);
+                        u64 cd[NR];
+                        col_mask(d2, cd);
+#pragma unroll
+                        for (int w = 0; w < NR; ++w) cd[w] &= F2[w];
+                        const int a1 = lowest(cd);
+                        const int d1 = mr_of(a1);
+                        set_mr(a2, f);
+                        set_mr(a1, d2);
+                        set_mr(r0, d1);
+                        done = true;
                     }
                 }
+                if (!done) {
+                    // deeper than three levels: let the general search redo it
+                    set_mr(r0, -1);
+#pragma unroll
+                    for (int w = 0; w < NR; ++w)
+                        if ((f >> 6) == w) FREEC[w] |= 1ull << (f & 63);
+                    if (!augment(r0)) status = -3;
+                }
             } else {
-                // ---- general path: unmatch every exhausted cell first, then re-augment in order
+                // ---- several exhausted cells: unmatch all of them first, then re-augment in order
                 u64 z[NR];
 #pragma unroll
                 for (int w = 0; w < NR; ++w) z[w] = Z[w];
@@ -399,20 +531,15 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     const int a = lowest(z);
                     const int d = mr_of(a);
                     const u64 bit = 1ull << (a & 63);
-                    const bool here = lane == (d & 63);
+                    clear_edge(a, d);
 #pragma unroll
-                    for (int k = 0; k < NR; ++k) {
-                        if ((d >> 6) == k) {
-#pragma unroll
-                            for (int w = 0; w < NR; ++w)
-                                if ((a >> 6) == w) cm[k][w] = here ? cm[k][w] & ~bit : cm[k][w];
-                            FREEC[k] |= 1ull << (d & 63);
-                        }
-                    }
+                    for (int k = 0; k < NR; ++k)
+                        if ((d >> 6) == k) FREEC[k] |= 1ull << (d & 63);
 #pragma unroll
                     for (int w = 0; w < NR; ++w)
                         if ((a >> 6) == w) z[w] &= ~bit;
                 }
+                masks_from_lds();
 #pragma unroll
                 for (int k = 0; k < NR; ++k) mr[k] = zero[k] ? -1 : mr[k];
                 bool ok = true;
@@ -426,8 +553,11 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         }
         if (lane == 0) out_num[b] = status < 0 ? status : s;
     };
-    if (narrow) run((u32)0);
-    else run((u64)0);
+    // the real bytes of a cell never exceed the largest entry of Q: 32-bit counters when that
+    // fits, whatever the virtual bytes make of the residuals
+    if (narrow) run((u32)0, (int32_t)0);
+    else if (qmax < ((i64)1 << 31)) run((u64)0, (int32_t)0);
+    else run((u64)0, (i64)0);
 }
 
 // One wavefront per matrix: matrix blockIdx.x.  COST: the same wavefront goes on to evaluate the

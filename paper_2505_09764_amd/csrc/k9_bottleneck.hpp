@@ -72,14 +72,15 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     const int lane = threadIdx.x;
 
     i64 diag[NR], PR[NR], ER[NR];
-    const i64 L = embed_into_lds<NR>(wsQ, wsPart, b, S, lane, R, PC, EC, diag, PR, ER);
+    i64 qmax = 0;      // largest entry of Q: not needed here
+    const i64 L = embed_into_lds<NR>(wsQ, wsPart, b, S, S, lane, R, PC, EC, diag, PR, ER, qmax);
     if (L <= 0) {
         if (lane == 0) out_num[b] = (int32_t)L;     // -1: invalid input, 0: nothing to send
         return;
     }
     const bool narrow = L < ((i64)1 << 31);
     if (narrow) {
-        repack_narrow<false>(R, S, lane);
+        repack_narrow<false>(R, S * S, lane);
     } else {
         for (int e = lane; e < S * S; e += 64) R[e] &= ~VFLAG;
         wave_sync();

@@ -134,28 +134,38 @@ __device__ __forceinline__ void column_mask(const u64 (&cm)[NR][NR], int d, u64 
 }
 
 // Embedding (paper Section 4.4 "Adapting an arbitrary matrix to a valid form"): loads the
-// per-lane matrix Q of matrix b into LDS, raises every line to L = the largest row/column sum
-// by virtual bytes - first on the diagonal, then row deficits poured into column deficits in
-// ascending order, which makes the virtual part of cell (a, d) the overlap of the prefix-sum
-// intervals [PR[a], ER[a]) and [PC[d], EC[d]) plus diag[a] on the diagonal - and leaves
-// R = Q + A in LDS, bit 63 set where a cell holds virtual bytes.  PR, ER, diag stay in
-// registers (per row of the lane), PC, EC go to LDS.
+// per-lane matrix Q of matrix b into LDS (row stride RS >= S words), raises every line to L =
+// the largest row/column sum by virtual bytes - first on the diagonal, then row deficits poured
+// into column deficits in ascending order, which makes the virtual part of cell (a, d) the
+// overlap of the prefix-sum intervals [PR[a], ER[a]) and [PC[d], EC[d]) plus diag[a] on the
+// diagonal - and leaves R = Q + A in LDS, bit 63 set where a cell holds virtual bytes.  PR, ER,
+// diag stay in registers (per row of the lane), PC, EC go to LDS.  qmax receives the largest
+// entry of Q (no cell ever holds more real bytes than that).
 // Returns -1 if kernel 1 flagged the matrix as invalid, else L (0: nothing to send).
 template <int NR>
 __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
-                                              const i64* __restrict__ wsPart, int b, int S,
+                                              const i64* __restrict__ wsPart, int b, int S, int RS,
                                               int lane, u64* R, i64* PC, i64* EC,
-                                              i64 (&diag)[NR], i64 (&PR)[NR], i64 (&ER)[NR]) {
+                                              i64 (&diag)[NR], i64 (&PR)[NR], i64 (&ER)[NR],
+                                              i64& qmax) {
     {
         int bad = 0;
         for (int a = lane; a < S; a += 64) bad |= (int)wsPart[((size_t)b * S + a) * K1_PART + 2];
         if (ballot(bad != 0)) return -1;
     }
     const i64* Qg = wsQ + (size_t)b * S * S;
-    for (int e = lane; e < S * S; e += 64) R[e] = (u64)Qg[e];
+    if (RS == S) {
+        for (int e = lane; e < S * S; e += 64) R[e] = (u64)Qg[e];
+    } else {
+        for (int e = lane; e < S * S; e += 64) {
+            const int a = e / S;
+            R[a * RS + (e - a * S)] = (u64)Qg[e];
+        }
+    }
     wave_sync();
 
     i64 rsum[NR], csum[NR];
+    i64 cellmax = 0;
 #pragma unroll
     for (int k = 0; k < NR; ++k) {
         const int x = lane + 64 * k;
@@ -165,11 +175,14 @@ __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
             for (int j = 0; j < S; ++j) {
                 int d = j + x;
                 d = d >= S ? d - S : d;
-                rsum[k] += (i64)R[(size_t)x * S + d];
-                csum[k] += (i64)R[(size_t)j * S + x];
+                const i64 v = (i64)R[x * RS + d];
+                rsum[k] += v;
+                cellmax = max(cellmax, v);
+                csum[k] += (i64)R[j * RS + x];
             }
         }
     }
+    qmax = (i64)uniform64((u64)wave_max_i64(cellmax));
     i64 lmax = 0;
 #pragma unroll
     for (int k = 0; k < NR; ++k) lmax = max(lmax, max(rsum[k], csum[k]));
@@ -208,14 +221,14 @@ __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
     for (int k = 0; k < NR; ++k) {
         const int x = lane + 64 * k;
         if (x < S) {
-            if (diag[k] > 0) R[(size_t)x * S + x] = (R[(size_t)x * S + x] + (u64)diag[k]) | VFLAG;
+            if (diag[k] > 0) R[x * RS + x] = (R[x * RS + x] + (u64)diag[k]) | VFLAG;
             if (ER[k] > PR[k]) {
                 for (int j = 0; j < S; ++j) {
                     int d = j + x;
                     d = d >= S ? d - S : d;
                     const i64 l = max(PR[k], PC[d]);
                     const i64 h = min(ER[k], EC[d]);
-                    if (h > l) R[(size_t)x * S + d] = (R[(size_t)x * S + d] + (u64)(h - l)) | VFLAG;
+                    if (h > l) R[x * RS + d] = (R[x * RS + d] + (u64)(h - l)) | VFLAG;
                 }
             }
         }
@@ -224,17 +237,17 @@ __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
     return L;
 }
 
-// No residual exceeds L, the largest line sum: when L < 2^31 the 64-bit words of R (S*S of them,
-// flag in bit 63) are repacked in place to 32-bit words (flag in bit 31, or dropped).
+// No residual exceeds L, the largest line sum: when L < 2^31 the n 64-bit words of R (flag in
+// bit 63) are repacked in place to 32-bit words (flag in bit 31, or dropped).
 template <bool KEEP_FLAG = true>
-__device__ __forceinline__ void repack_narrow(u64* R, int S, int lane) {
+__device__ __forceinline__ void repack_narrow(u64* R, int n, int lane) {
     u32* R32 = reinterpret_cast<u32*>(R);
-    for (int e0 = 0; e0 < S * S; e0 += 64) {
+    for (int e0 = 0; e0 < n; e0 += 64) {
         const int e = e0 + lane;
         u64 v = 0;
-        if (e < S * S) v = R[e];
+        if (e < n) v = R[e];
         wave_sync();                    // chunk read before its (lower) words are rewritten
-        if (e < S * S) R32[e] = (u32)v | ((KEEP_FLAG && (v & VFLAG)) ? 0x80000000u : 0u);
+        if (e < n) R32[e] = (u32)v | ((KEEP_FLAG && (v & VFLAG)) ? 0x80000000u : 0u);
     }
     wave_sync();
 }
