@@ -291,8 +291,8 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         i64* cw = wsC + (size_t)b * max_stages;
         i64 Lrem = L;
         int s = 0;
-        int32_t* srow = stg;
-        i64* brow = byt;
+        // byte offsets of the lane's first slot in the stage row being written
+        u32 soff = (u32)lane * 4u, boff = (u32)lane * 8u, coff = 0;
         // mr of a uniform row
         auto mr_of = [&](int a) -> int {
             if constexpr (NR == 2) {
@@ -346,7 +346,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 #pragma unroll
             for (int k = 0; k < NR; ++k) Rv[rowbase[k] + (u32)mr[k]] = with_flag(rv[k], vfl[k]);
         };
-        enum { GO_ON = 0, DONE, OVERFLOW, GENERAL, DEEP };
+        enum { GO_ON = 0, DONE, GENERAL, DEEP };
         for (;;) {
             // ---- the stages that end in a two-level repair run in this inner loop; anything
             // else leaves it with a reason and is handled below
@@ -354,8 +354,8 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             u64 Z[NR];
             bool zero[NR];
             int r0 = 0, f = 0;
+            if (__builtin_expect(s >= max_stages, 0)) { status = -2; break; }
             do {
-                if (__builtin_expect(s >= max_stages, 0)) { why = OVERFLOW; break; }
                 V mine = (V)rv[0];
                 if constexpr (NR == 2) mine = (V)rv[1] < mine ? (V)rv[1] : mine;
                 const i64 c64 = (i64)wave_min(mine);    // stage weight: wave-uniform, fits SV
@@ -380,16 +380,20 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     rl[k] -= real;
                     rv[k] -= c;
                     if (FULL || lid[k] < S) {
-                        srow[(u32)lid[k]] = real > 0 ? mr[k] : -1;
-                        brow[(u32)lid[k]] = (i64)(std::make_unsigned_t<RL>)real;
+                        *reinterpret_cast<int32_t*>(reinterpret_cast<char*>(stg) + soff + 256u * k) =
+                            real > 0 ? mr[k] : -1;
+                        *reinterpret_cast<i64*>(reinterpret_cast<char*>(byt) + boff + 512u * k) =
+                            (i64)(std::make_unsigned_t<RL>)real;
                     }
                     zero[k] = rv[k] == 0;
                     Z[k] = ballot(zero[k]);
                 }
-                cw[s] = (i64)c;   // every lane stores the same word: no divergent branch on the path
+                // every lane stores the same word: no divergent branch on the path
+                *reinterpret_cast<i64*>(reinterpret_cast<char*>(cw) + coff) = (i64)c;
                 ++s;
-                srow += S;
-                brow += S;
+                soff += 4u * (u32)S;
+                boff += 8u * (u32)S;
+                coff += 8u;
                 Lrem -= c64;
                 if (__builtin_expect(Lrem == 0, 0)) { why = DONE; break; }
                 if constexpr (!LATE_WRITE_BACK) write_back();
@@ -455,7 +459,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     rv[k] = ch ? (SV)val : rv[k];
                     rl[k] = ch ? (RL)val : rl[k];
                     vfl[k] = ch ? fl : vfl[k];
-                    anyv |= ballot(ch) & ballot((SV)x < 0);
+                    anyv |= (ballot(isA) | ballot(isR)) & ballot((SV)x < 0);
                     mr[k] = isA ? f : (isR ? d1 : mr[k]);
                 }
                 if (__builtin_expect(anyv != 0, 0)) {
@@ -470,9 +474,9 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                         }
                     }
                 }
-            } while (true);
+            } while (__builtin_expect(s < max_stages, 1));
             if (why == DONE) break;
-            if (why == OVERFLOW) { status = -2; break; }
+            if (why == GO_ON) { status = -2; break; }       // out of stage rows
 #pragma unroll
             for (int k = 0; k < NR; ++k) loaded[k] = mr[k];     // what LDS and the registers describe
             if (why == DEEP) {
