@@ -10,8 +10,10 @@ quoted on.  Prints ONE JSON line:
   value          schedules synthesised per second = B * steps / timed seconds
   p50/p99_us_per_schedule   per-step time / B
   kernels_ms     average duration of each kernel (HIP events on the launch stream)
-  roofline       the streaming kernel (aggregation + balancing) against HBM peak
-  stage_loop     the decomposition kernel, which is bound by its serial stage chain
+  roofline       the dominant kernel (the decomposition, 98 % of a step) against the issue
+                 rate of its one wavefront per matrix
+  roofline_hbm   the streaming kernel (aggregation + balancing) against HBM peak
+  stage_loop     the decomposition kernel per stage: measured ns, floor of its instruction stream
   cpu_baseline   the CPU oracle timed on this machine's host cores on a bounded sample
   latency_b1     the same configuration at B = 1 (true single-matrix latency)
   spreadout_baseline  time of the SpreadOut comparison pass and predicted-time ratios
@@ -37,6 +39,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak, GB/s
+CLOCK_HZ = 2.4e9               # MI355X engine clock
 
 
 def percentile(xs, q):
@@ -196,6 +199,15 @@ def main():
     prof = os.path.join(ROOT, "profiles", f"k1_rebalance_cfg{args.config}_hbm_traffic.json")
     if os.path.exists(prof) and B == w.B:
         measured = json.load(open(prof)).get("hbm_bytes_per_launch")
+    # Ceiling of the decomposition kernel: one wavefront per matrix walks a serial chain of
+    # stages, and a wavefront issues at most one instruction per four clock cycles, so the
+    # issue slots a stage occupies (counted by rocprofv3, committed under profiles/) are its
+    # floor; peak = that floor turned into stages per second, for the B wavefronts of a launch.
+    k2_slots = k2_insts = None
+    prof2 = os.path.join(ROOT, "profiles", f"k2_birkhoff_cfg{args.config}_stage_counters.json")
+    if os.path.exists(prof2):
+        pj = json.load(open(prof2))
+        k2_slots, k2_insts = pj["active_quad_cycles_per_stage"], pj["instructions_per_stage"]
 
     # true single-matrix latency of the same configuration
     lat = None
@@ -325,12 +337,31 @@ def main():
         "p99_us_per_schedule": percentile(per_sched_us, 0.99),
         "stages_per_schedule_mean": stages_total / B,
         "kernels_ms": {"k1_rebalance": k_avg[0], "k2_birkhoff": k_avg[1], "k3_cost": k_avg[2]},
-        "roofline": {"kernel": "k1_rebalance", "bound": "hbm", "achieved": k1_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k1_gbs / HBM_PEAK_GBS,
-                     "traffic": measured, "algorithmic_bytes": k1_bytes},
-        "stage_loop": {"kernel": "k2_birkhoff", "bound": "serial stage chain (latency)",
+        # the dominant kernel (98 % of a step): bound by the instruction issue of one wavefront
+        # per matrix, a serial chain of stages
+        "roofline": {"kernel": "k2_birkhoff", "bound": "alu",
+                     "achieved": float(K.sum()) / (k_avg[1] * 1e-3),
+                     "peak": (B * CLOCK_HZ / (4.0 * k2_slots)) if k2_slots else None,
+                     "unit": "stages/s",
+                     "frac": (float(K.sum()) / (k_avg[1] * 1e-3)) / (B * CLOCK_HZ / (4.0 * k2_slots))
+                     if k2_slots else None,
+                     "traffic": None,
+                     "issue_slots_per_stage": k2_slots, "instructions_per_stage": k2_insts,
+                     "wavefronts": B,
+                     "note": "peak = one instruction per 4 clocks per wavefront at 2.4 GHz over the "
+                             "issue slots of a stage (profiles/k2_birkhoff_cfg5_stage_counters.md); "
+                             "achieved averages over the matrices of the launch, which run in "
+                             "parallel and end with the longest"},
+        # the streaming kernel, the one the HBM-bandwidth target applies to
+        "roofline_hbm": {"kernel": "k1_rebalance", "bound": "hbm", "achieved": k1_gbs,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k1_gbs / HBM_PEAK_GBS,
+                         "traffic": measured, "algorithmic_bytes": k1_bytes},
+        "stage_loop": {"kernel": "k2_birkhoff", "bound": "serial stage chain (instruction issue)",
                        "stages_per_sec_per_matrix": (K.max() / (k_avg[1] * 1e-3)),
                        "ns_per_stage": k_avg[1] * 1e6 / K.max(),
+                       "ceiling_ns_per_stage": (4.0 * k2_slots / CLOCK_HZ * 1e9) if k2_slots else None,
+                       "frac": (4.0 * k2_slots / CLOCK_HZ * 1e9) / (k_avg[1] * 1e6 / K.max())
+                       if k2_slots else None,
                        "achieved_GBs": k2_bytes / (k_avg[1] * 1e-3) / 1e9,
                        "algorithmic_bytes": k2_bytes},
         "end_to_end_GBs": (k1_bytes + k2_bytes + k3_bytes) / (ms_per_step * 1e-3) / 1e9,

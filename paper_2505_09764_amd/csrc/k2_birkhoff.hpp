@@ -106,7 +106,8 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 
     i64 diag[NR], PR[NR], ER[NR];
     i64 qmax = 0;
-    const i64 L = embed_into_lds<NR>(wsQ, wsPart, b, S, RS, lane, R, PC, EC, diag, PR, ER, qmax);
+    int sh = 0;         // every byte count below is in units of 2^sh bytes (0 unless that makes L fit 31 bits)
+    const i64 L = embed_into_lds<NR>(wsQ, wsPart, b, S, RS, lane, R, PC, EC, diag, PR, ER, qmax, sh);
     if (L <= 0) {
         if (lane == 0) out_num[b] = (int32_t)L;     // -1: invalid input, 0: nothing to send
         return;
@@ -383,13 +384,13 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                         *reinterpret_cast<int32_t*>(reinterpret_cast<char*>(stg) + soff + 256u * k) =
                             real > 0 ? mr[k] : -1;
                         *reinterpret_cast<i64*>(reinterpret_cast<char*>(byt) + boff + 512u * k) =
-                            (i64)(std::make_unsigned_t<RL>)real;
+                            (i64)(std::make_unsigned_t<RL>)real << sh;
                     }
                     zero[k] = rv[k] == 0;
                     Z[k] = ballot(zero[k]);
                 }
                 // every lane stores the same word: no divergent branch on the path
-                *reinterpret_cast<i64*>(reinterpret_cast<char*>(cw) + coff) = (i64)c;
+                *reinterpret_cast<i64*>(reinterpret_cast<char*>(cw) + coff) = (i64)c << sh;
                 ++s;
                 soff += 4u * (u32)S;
                 boff += 8u * (u32)S;

@@ -73,7 +73,8 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 
     i64 diag[NR], PR[NR], ER[NR];
     i64 qmax = 0;      // largest entry of Q: not needed here
-    const i64 L = embed_into_lds<NR>(wsQ, wsPart, b, S, S, lane, R, PC, EC, diag, PR, ER, qmax);
+    int sh = 0;        // byte counts are in units of 2^sh bytes (0 unless that makes L fit 31 bits)
+    const i64 L = embed_into_lds<NR>(wsQ, wsPart, b, S, S, lane, R, PC, EC, diag, PR, ER, qmax, sh);
     if (L <= 0) {
         if (lane == 0) out_num[b] = (int32_t)L;     // -1: invalid input, 0: nothing to send
         return;
@@ -467,7 +468,7 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     const i64 real_left = (i64)v > av ? (i64)v - av : 0;
                     const i64 real = min((i64)c, real_left);
                     srow[row[k]] = real > 0 ? d : -1;
-                    brow[row[k]] = real;
+                    brow[row[k]] = real << sh;
                     const V left = v - c;
                     Rv[rowbase[k] + (u32)d] = left;
                     if constexpr (WIDE) cross = (v >> 32) != 0 && (left >> 32) == 0;
@@ -485,7 +486,7 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                             if ((d >> 6) == k && lane == (d & 63)) big[k][kr] &= ~(1ull << al);
                     }
             }
-            if (lane == 0) cw[s] = (i64)c;
+            if (lane == 0) cw[s] = (i64)c << sh;
             ++s;
             srow += S;
             brow += S;

@@ -141,25 +141,40 @@ __device__ __forceinline__ void column_mask(const u64 (&cm)[NR][NR], int d, u64 
 // diagonal - and leaves R = Q + A in LDS, bit 63 set where a cell holds virtual bytes.  PR, ER,
 // diag stay in registers (per row of the lane), PC, EC go to LDS.  qmax receives the largest
 // entry of Q (no cell ever holds more real bytes than that).
-// Returns -1 if kernel 1 flagged the matrix as invalid, else L (0: nothing to send).
+// Common factor: when L does not fit 31 bits but every entry of Q is a multiple of 2^sh and
+// L / 2^sh does, the whole matrix is divided by 2^sh (sh is returned; 0 otherwise).  Sums,
+// deficits and virtual bytes are multiples of 2^sh as well, the decomposition of the divided
+// matrix is the decomposition of the original with every byte count divided by 2^sh, so the
+// caller runs on 32-bit words and shifts the byte counts it emits back.  Traffic built from
+// whole tokens is of that kind: every entry a multiple of the token size.
+// Returns -1 if kernel 1 flagged the matrix as invalid, else L (0: nothing to send), divided
+// by 2^sh like everything else.
 template <int NR>
 __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
                                               const i64* __restrict__ wsPart, int b, int S, int RS,
                                               int lane, u64* R, i64* PC, i64* EC,
                                               i64 (&diag)[NR], i64 (&PR)[NR], i64 (&ER)[NR],
-                                              i64& qmax) {
+                                              i64& qmax, int& sh) {
+    sh = 0;
     {
         int bad = 0;
         for (int a = lane; a < S; a += 64) bad |= (int)wsPart[((size_t)b * S + a) * K1_PART + 2];
         if (ballot(bad != 0)) return -1;
     }
     const i64* Qg = wsQ + (size_t)b * S * S;
+    u64 bits = 0;       // OR of the lane's entries: its trailing zeros are common to all of them
     if (RS == S) {
-        for (int e = lane; e < S * S; e += 64) R[e] = (u64)Qg[e];
+        for (int e = lane; e < S * S; e += 64) {
+            const u64 v = (u64)Qg[e];
+            R[e] = v;
+            bits |= v;
+        }
     } else {
         for (int e = lane; e < S * S; e += 64) {
             const int a = e / S;
-            R[a * RS + (e - a * S)] = (u64)Qg[e];
+            const u64 v = (u64)Qg[e];
+            R[a * RS + (e - a * S)] = v;
+            bits |= v;
         }
     }
     wave_sync();
@@ -186,8 +201,22 @@ __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
     i64 lmax = 0;
 #pragma unroll
     for (int k = 0; k < NR; ++k) lmax = max(lmax, max(rsum[k], csum[k]));
-    const i64 L = (i64)uniform64((u64)wave_max_i64(lmax));
+    i64 L = (i64)uniform64((u64)wave_max_i64(lmax));
     if (L == 0) return 0;
+    if (L >= ((i64)1 << 31)) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) bits |= (u64)__shfl_xor((i64)bits, off, 64);
+        const int tz = __builtin_ctzll(uniform64(bits));        // bits != 0 because L > 0
+        if (tz > 0 && (L >> tz) < ((i64)1 << 31)) {
+            sh = tz;
+            for (int e = lane; e < S * RS; e += 64) R[e] >>= tz;     // pad words of a row included
+            L >>= tz;
+            qmax >>= tz;
+#pragma unroll
+            for (int k = 0; k < NR; ++k) { rsum[k] >>= tz; csum[k] >>= tz; }
+            wave_sync();
+        }
+    }
 
     {
         i64 dr[NR], dc[NR];

@@ -295,6 +295,33 @@ def test_residual_width_boundary(oracle, torch_cuda):
         assert int(r["K"][0]) == 1 and int(r["bytes"][0, 0].max()) == q
 
 
+@pytest.mark.parametrize("S,G", [(5, 2), (16, 8), (70, 4), (128, 1)])
+def test_common_power_of_two_factor(oracle, torch_cuda, S, G):
+    """When the largest line sum needs more than 31 bits but every per-lane entry shares a
+    factor 2^k that brings it under, the decomposition runs on the divided matrix and shifts
+    its byte counts back: matrices whose entries are multiples of 2^k for several k, on both
+    sides of "the divided sum fits", for both decomposition rules."""
+    N = S * G
+    rng = np.random.default_rng(4000 + S)
+    mats = []
+    # (multiple of, rough size of an entry): the largest line sum is about S * G * entry
+    for unit, top in [(1 << 12, 1 << 34), (1 << 1, 1 << 33), (1 << 3, 1 << 35), (1 << 40, 1 << 50),
+                      (14336, 1 << 33), (1, 1 << 33), (1 << 20, 1 << 30)]:
+        t = (rng.integers(0, max(top // (unit * S * G), 2), size=(N, N)) * unit).astype(np.int64)
+        t[rng.random((N, N)) < 0.3] = 0
+        # per-lane entries are ceil(tile total / G): keep the tile totals multiples of G * unit
+        t4 = t.reshape(S, G, S, G)
+        t4[:, 1:, :, :] = 0
+        t4 *= G
+        mats.append(t)
+    tr = np.stack(mats)
+    say(f"[parity] common factor S={S} G={G}")
+    for matching in (None, "bottleneck"):
+        res = run_gpu(torch_cuda, S, G, 400e9, 50e9, tr, matching=matching)
+        assert (res["K"] > 0).all()
+        compare_batch(oracle, S, G, 400e9, 50e9, tr, res, bottleneck=matching is not None)
+
+
 def test_negative_entry_status_is_per_matrix(oracle, torch_cuda):
     S, G = 4, 8
     rng = np.random.default_rng(5)
