@@ -347,6 +347,30 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 #pragma unroll
             for (int k = 0; k < NR; ++k) Rv[rowbase[k] + (u32)mr[k]] = with_flag(rv[k], vfl[k]);
         };
+        // x of the lane slot that holds row a (a wave-uniform), as a wave-uniform value
+        auto value_of_row = [&](const V (&x)[NR], int a) -> V {
+            if constexpr (NR == 2) {
+                if constexpr (sizeof(V) == 8) {
+                    const u64 b0 = rdl64((u64)x[0], a & 63), b1 = rdl64((u64)x[1], a & 63);
+                    return (V)((a & 64) ? b1 : b0);
+                } else {
+                    const u32 b0 = rdl((u32)x[0], a & 63), b1 = rdl((u32)x[1], a & 63);
+                    return (V)((a & 64) ? b1 : b0);
+                }
+            } else {
+                if constexpr (sizeof(V) == 8) return (V)rdl64((u64)x[0], a);
+                else return (V)rdl((u32)x[0], a);
+            }
+        };
+        // a cell's word without its flag bit, folded to 32 bits: non-zero while the cell is positive
+        auto fold = [&](V x) -> u32 {
+            if constexpr (sizeof(V) == 8) return ((u32)((u64)x >> 32) & 0x7FFFFFFFu) | (u32)x;
+            else return (u32)x & 0x7FFFFFFFu;
+        };
+        // Whether a three-level repair is worked out from the reads of the stage plus one more
+        // column read, or on the support masks alone: measured, the first wins when a lane holds
+        // two rows and loses when it holds one.
+        constexpr bool DEEP_FROM_READS = NR == 2;
         enum { GO_ON = 0, DONE, GENERAL, DEEP };
         for (;;) {
             // ---- the stages that end in a two-level repair run in this inner loop; anything
@@ -355,6 +379,9 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             u64 Z[NR];
             bool zero[NR];
             int r0 = 0, f = 0;
+            V ea[NR], eb[NR];      // R[row][f] and R[r0][column of the row], read by the stage that left
+#pragma unroll
+            for (int k = 0; k < NR; ++k) ea[k] = eb[k] = 0;
             if (__builtin_expect(s >= max_stages, 0)) { status = -2; break; }
             do {
                 V mine = (V)rv[0];
@@ -408,7 +435,6 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 // read by a1's lane are the ones that get matched.
                 r0 = lowest(Z);
                 f = mr_of(r0);
-                V ea[NR], eb[NR];
 #pragma unroll
                 for (int k = 0; k < NR; ++k) {
                     ea[k] = Rv[rowbase[k] + (u32)f];
@@ -419,16 +445,8 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 u64 c2[NR];
 #pragma unroll
                 for (int k = 0; k < NR; ++k) {
-                    // both cells positive (flag bit aside): fold each to 32 bits, take the smaller
-                    u32 fa, fb;
-                    if constexpr (sizeof(V) == 8) {
-                        fa = ((u32)((u64)ea[k] >> 32) & 0x7FFFFFFFu) | (u32)ea[k];
-                        fb = ((u32)((u64)eb[k] >> 32) & 0x7FFFFFFFu) | (u32)eb[k];
-                    } else {
-                        fa = (u32)ea[k] & 0x7FFFFFFFu;
-                        fb = (u32)eb[k] & 0x7FFFFFFFu;
-                    }
-                    c2[k] = ballot(min(fa, fb) != 0);
+                    // both cells positive: fold each to 32 bits, take the smaller
+                    c2[k] = ballot(min(fold(ea[k]), fold(eb[k])) != 0);
                     if constexpr (LATE_WRITE_BACK)
                         if ((r0 >> 6) == k) c2[k] &= ~(1ull << (r0 & 63));     // its cell (r0, f) was read stale
                     if constexpr (!FULL) c2[k] &= LIVE[k];
@@ -436,19 +454,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 if (__builtin_expect(!any(c2), 0)) { why = DEEP; break; }
                 const int a1 = lowest(c2);
                 const int d1 = mr_of(a1);
-                V vb;
-                if constexpr (NR == 2) {
-                    if constexpr (sizeof(V) == 8) {
-                        const u64 b0 = rdl64((u64)eb[0], a1 & 63), b1 = rdl64((u64)eb[1], a1 & 63);
-                        vb = (V)((a1 & 64) ? b1 : b0);
-                    } else {
-                        const u32 b0 = rdl((u32)eb[0], a1 & 63), b1 = rdl((u32)eb[1], a1 & 63);
-                        vb = (V)((a1 & 64) ? b1 : b0);
-                    }
-                } else {
-                    if constexpr (sizeof(V) == 8) vb = (V)rdl64((u64)eb[0], a1);
-                    else vb = (V)rdl((u32)eb[0], a1);
-                }
+                const V vb = value_of_row(eb, a1);
                 u64 anyv = 0;
 #pragma unroll
                 for (int k = 0; k < NR; ++k) {
@@ -481,51 +487,128 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 #pragma unroll
             for (int k = 0; k < NR; ++k) loaded[k] = mr[k];     // what LDS and the registers describe
             if (why == DEEP) {
-                // not a two-level repair: level three in straight-line code on the masks,
-                // anything deeper through the general search
-                masks_from_lds();
-                const u64 bit0 = 1ull << (r0 & 63);
-                u64 cmf[NR], N1[NR], F2[NR];
-                col_mask(f, cmf);
-                {
-                    u64 F1[NR];
+                if constexpr (DEEP_FROM_READS) {
+                    // Not a two-level repair.  Level three, still in straight-line code: the reads of
+                    // the stage say which rows have a cell in column f (cmf) and which are matched
+                    // into a column that row r0 reaches (F2, the second frontier); the support masks
+                    // give the columns that F2 reaches (N2) and with them the third frontier; the
+                    // lowest of its rows with a cell in column f is a2, and one more column read
+                    // finds a2's parent a1 in F2 - and is the cell a1 gets matched to.
+                    u64 cmf[NR], F2[NR];
 #pragma unroll
-                    for (int w = 0; w < NR; ++w) F1[w] = (r0 >> 6) == w ? bit0 : 0ull;
-                    expand(F1, N1);
-                    rows_matched_into(N1, F2);
-                }
-                bool done = false;
-                if (any(N1)) {
-                    set_mr(r0, -1);
-                    u64 N2[NR], F3[NR], c3[NR];
-                    expand(F2, N2);
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) N2[w] &= ~N1[w];
-                    rows_matched_into(N2, F3);
-#pragma unroll
-                    for (int w = 0; w < NR; ++w) c3[w] = cmf[w] & F3[w];
-                    if (any(c3)) {
-                        const int a2 = lowest(c3);
-                        const int d2 = mr_of(a2);
-                        u64 cd[NR];
-                        col_mask(d2, cd);
-#pragma unroll
-                        for (int w = 0; w < NR; ++w) cd[w] &= F2[w];
-                        const int a1 = lowest(cd);
-                        const int d1 = mr_of(a1);
-                        set_mr(a2, f);
-                        set_mr(a1, d2);
-                        set_mr(r0, d1);
-                        done = true;
+                    for (int k = 0; k < NR; ++k) {
+                        const u64 notr0 = (r0 >> 6) == k ? ~(1ull << (r0 & 63)) : ~0ull;
+                        cmf[k] = ballot(fold(ea[k]) != 0) & notr0;
+                        F2[k] = ballot(fold(eb[k]) != 0) & notr0;
+                        if constexpr (!FULL) { cmf[k] &= LIVE[k]; F2[k] &= LIVE[k]; }
                     }
-                }
-                if (!done) {
+                    masks_from_lds();
+                    bool done = false;
+                    if (any(F2)) {
+                        u64 N2[NR], F3[NR], c3[NR];
+                        expand(F2, N2);
+                        rows_matched_into(N2, F3);
+                        // rows matched into a column that r0 reaches itself are on level two already
+#pragma unroll
+                        for (int w = 0; w < NR; ++w) c3[w] = cmf[w] & F3[w] & ~F2[w];
+                        if (any(c3)) {
+                            const int a2 = lowest(c3);
+                            const int d2 = mr_of(a2);
+                            V ec[NR];
+                            u64 c1[NR];
+#pragma unroll
+                            for (int k = 0; k < NR; ++k) {
+                                ec[k] = Rv[rowbase[k] + (u32)d2];
+                                c1[k] = F2[k] & ballot(fold(ec[k]) != 0);
+                            }
+                            if (any(c1)) {
+                                const int a1 = lowest(c1);
+                                const int d1 = mr_of(a1);
+                                const V vb = value_of_row(eb, a1);
+                                u64 anyv = 0;
+#pragma unroll
+                                for (int k = 0; k < NR; ++k) {
+                                    const bool isA2 = lid[k] == a2, isA1 = lid[k] == a1, isR = lid[k] == r0;
+                                    const V x = isA2 ? ea[k] : (isA1 ? ec[k] : vb);
+                                    const bool ch = isA2 || isA1 || isR;
+                                    const V val = x & (V)~VF;
+                                    const u32 fl = flag_of(x);
+                                    rv[k] = ch ? (SV)val : rv[k];
+                                    rl[k] = ch ? (RL)val : rl[k];
+                                    vfl[k] = ch ? fl : vfl[k];
+                                    anyv |= ballot(ch && fl != 0);
+                                    mr[k] = isA2 ? f : (isA1 ? d2 : (isR ? d1 : mr[k]));
+                                }
+                                if (anyv != 0) {
+#pragma unroll
+                                    for (int k = 0; k < NR; ++k) {
+                                        if ((lid[k] == a2 || lid[k] == a1 || lid[k] == r0) && vfl[k] != 0) {
+                                            const int d = mr[k];
+                                            const i64 l = max(PR[k], PC[d]);
+                                            const i64 h = min(ER[k], EC[d]);
+                                            const i64 av = (h > l ? h - l : 0) + (d == lid[k] ? diag[k] : 0);
+                                            rl[k] = (i64)rv[k] > av ? (RL)((i64)rv[k] - av) : (RL)0;
+                                        }
+                                    }
+                                }
+                                done = true;
+                            }
+                        }
+                    }
+                    if (done) continue;     // LDS and the registers agree: on to the next stage
                     // deeper than three levels: let the general search redo it
                     set_mr(r0, -1);
 #pragma unroll
                     for (int w = 0; w < NR; ++w)
                         if ((f >> 6) == w) FREEC[w] |= 1ull << (f & 63);
                     if (!augment(r0)) status = -3;
+                } else {
+                    // not a two-level repair: level three in straight-line code on the masks,
+                    // anything deeper through the general search
+                    masks_from_lds();
+                    const u64 bit0 = 1ull << (r0 & 63);
+                    u64 cmf[NR], N1[NR], F2[NR];
+                    col_mask(f, cmf);
+                    {
+                        u64 F1[NR];
+#pragma unroll
+                        for (int w = 0; w < NR; ++w) F1[w] = (r0 >> 6) == w ? bit0 : 0ull;
+                        expand(F1, N1);
+                        rows_matched_into(N1, F2);
+                    }
+                    bool done = false;
+                    if (any(N1)) {
+                        set_mr(r0, -1);
+                        u64 N2[NR], F3[NR], c3[NR];
+                        expand(F2, N2);
+#pragma unroll
+                        for (int w = 0; w < NR; ++w) N2[w] &= ~N1[w];
+                        rows_matched_into(N2, F3);
+#pragma unroll
+                        for (int w = 0; w < NR; ++w) c3[w] = cmf[w] & F3[w];
+                        if (any(c3)) {
+                            const int a2 = lowest(c3);
+                            const int d2 = mr_of(a2);
+                            u64 cd[NR];
+                            col_mask(d2, cd);
+#pragma unroll
+                            for (int w = 0; w < NR; ++w) cd[w] &= F2[w];
+                            const int a1 = lowest(cd);
+                            const int d1 = mr_of(a1);
+                            set_mr(a2, f);
+                            set_mr(a1, d2);
+                            set_mr(r0, d1);
+                            done = true;
+                        }
+                    }
+                    if (!done) {
+                        // deeper than three levels: let the general search redo it
+                        set_mr(r0, -1);
+#pragma unroll
+                        for (int w = 0; w < NR; ++w)
+                            if ((f >> 6) == w) FREEC[w] |= 1ull << (f & 63);
+                        if (!augment(r0)) status = -3;
+                    }
                 }
             } else {
                 // ---- several exhausted cells: unmatch all of them first, then re-augment in order
