@@ -371,6 +371,8 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         // column read, or on the support masks alone: measured, the first wins when a lane holds
         // two rows and loses when it holds one.
         constexpr bool DEEP_FROM_READS = NR == 2;
+        // two exhausted cells repaired on reads of R: measured, a gain only with two rows per lane
+        constexpr bool PAIR_FROM_READS = NR == 2;
         enum { GO_ON = 0, DONE, GENERAL, DEEP };
         for (;;) {
             // ---- the stages that end in a two-level repair run in this inner loop; anything
@@ -378,7 +380,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             int why = GO_ON;
             u64 Z[NR];
             bool zero[NR];
-            int r0 = 0, f = 0;
+            int r0 = 0, f = 0, nz = 0;
             V ea[NR], eb[NR];      // R[row][f] and R[r0][column of the row], read by the stage that left
 #pragma unroll
             for (int k = 0; k < NR; ++k) ea[k] = eb[k] = 0;
@@ -425,7 +427,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 Lrem -= c64;
                 if (__builtin_expect(Lrem == 0, 0)) { why = DONE; break; }
                 if constexpr (!LATE_WRITE_BACK) write_back();
-                int nz = 0;
+                nz = 0;
 #pragma unroll
                 for (int w = 0; w < NR; ++w) nz += __builtin_popcountll(Z[w]);
                 if (__builtin_expect(nz != 1, 0)) { why = GENERAL; break; }
@@ -611,30 +613,160 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     }
                 }
             } else {
-                // ---- several exhausted cells: unmatch all of them first, then re-augment in order
-                u64 z[NR];
+                // ---- several exhausted cells: all of them are unmatched first, then the rows are
+                // re-augmented in ascending order.  Two cells (rA, fA), (rB, fB) with rA < rB - by far
+                // the most frequent case - are repaired like the single cell, on reads of R, as long
+                // as each row's augmenting path has one or two levels: rA takes fB if it has a cell
+                // there, otherwise the lowest free column that its second frontier reaches; rB then
+                // takes the column left over, directly or through the second frontier under the
+                // matching as it stands by then.  Whatever that does not settle goes to the search.
+                int pending = (PAIR_FROM_READS && nz == 2) ? 2 : 3;     // 0: repaired, 1: second row left to the search, 3: everything
+                if (PAIR_FROM_READS && nz == 2) {
+                    u64 zz[NR];
 #pragma unroll
-                for (int w = 0; w < NR; ++w) z[w] = Z[w];
-                while (any(z)) {
-                    const int a = lowest(z);
-                    const int d = mr_of(a);
-                    const u64 bit = 1ull << (a & 63);
-                    clear_edge(a, d);
-#pragma unroll
-                    for (int k = 0; k < NR; ++k)
-                        if ((d >> 6) == k) FREEC[k] |= 1ull << (d & 63);
+                    for (int w = 0; w < NR; ++w) zz[w] = Z[w];
+                    const int rA = lowest(zz);
 #pragma unroll
                     for (int w = 0; w < NR; ++w)
-                        if ((a >> 6) == w) z[w] &= ~bit;
+                        if ((rA >> 6) == w) zz[w] &= ~(1ull << (rA & 63));
+                    const int rB = lowest(zz);
+                    const int fA = mr_of(rA), fB = mr_of(rB);
+                    if constexpr (LATE_WRITE_BACK) write_back();
+                    clear_edge(rA, fA);
+                    clear_edge(rB, fB);
+                    V xa[NR], xb[NR], ya[NR];       // columns fA, fB; row rA along the matching
+                    u64 others[NR];                 // rows that hold a matched cell
+#pragma unroll
+                    for (int k = 0; k < NR; ++k) {
+                        xa[k] = Rv[rowbase[k] + (u32)fA];
+                        xb[k] = Rv[rowbase[k] + (u32)fB];
+                        ya[k] = Rv[(u32)rA * (u32)RS + (u32)(FULL ? mr[k] : max(mr[k], 0))];
+                        others[k] = ~Z[k];
+                        if constexpr (!FULL) others[k] &= LIVE[k];
+                    }
+                    bool chg[NR];
+#pragma unroll
+                    for (int k = 0; k < NR; ++k) chg[k] = false;
+                    // row `row` (wave-uniform) is matched to column `col`, whose word in R is x
+                    auto rematch = [&](int row, int col, V x) {
+                        const V val = x & (V)~VF;
+                        const u32 fl = flag_of(x);
+#pragma unroll
+                        for (int k = 0; k < NR; ++k) {
+                            const bool me = lid[k] == row;
+                            rv[k] = me ? (SV)val : rv[k];
+                            rl[k] = me ? (RL)val : rl[k];
+                            vfl[k] = me ? fl : vfl[k];
+                            mr[k] = me ? col : mr[k];
+                            chg[k] = chg[k] || me;
+                        }
+                    };
+                    int fx = -1;                    // the column still free after the first row
+                    const V yAB = value_of_row(ya, rB);     // R[rA][fB]: rB's register still names fB
+                    if (fold(yAB) != 0) {
+                        rematch(rA, fB, yAB);
+                        fx = fA;
+                    } else {
+                        u64 ca[NR], cb[NR];         // second-frontier rows with a cell in fA / in fB
+#pragma unroll
+                        for (int k = 0; k < NR; ++k) {
+                            const u64 F2 = ballot(fold(ya[k]) != 0) & others[k];
+                            ca[k] = F2 & ballot(fold(xa[k]) != 0);
+                            cb[k] = F2 & ballot(fold(xb[k]) != 0);
+                        }
+                        const bool ra = any(ca), rb = any(cb);
+                        if (ra || rb) {
+                            const bool takeA = ra && (!rb || fA < fB);      // the lower free column
+                            int a1;
+                            V va1;
+                            if (takeA) { a1 = lowest(ca); va1 = value_of_row(xa, a1); }
+                            else { a1 = lowest(cb); va1 = value_of_row(xb, a1); }
+                            const int d1 = mr_of(a1);
+                            const V vA = value_of_row(ya, a1);
+                            rematch(a1, takeA ? fA : fB, va1);
+                            rematch(rA, d1, vA);
+                            fx = takeA ? fB : fA;
+                        }
+                    }
+                    if (fx >= 0) {
+                        pending = 1;
+                        const bool isA = fx == fA;
+                        const V xB = isA ? value_of_row(xa, rB) : value_of_row(xb, rB);     // R[rB][fx]
+                        if (fold(xB) != 0) {
+                            rematch(rB, fx, xB);
+                            pending = 0;
+                        } else {
+                            V yb[NR];               // row rB along the matching as it is now
+                            u64 c[NR];
+#pragma unroll
+                            for (int k = 0; k < NR; ++k) {
+                                yb[k] = Rv[(u32)rB * (u32)RS + (u32)(FULL ? mr[k] : max(mr[k], 0))];
+                                const V xk = isA ? xa[k] : xb[k];
+                                u64 m = ballot(min(fold(yb[k]), fold(xk)) != 0);
+                                if ((rB >> 6) == k) m &= ~(1ull << (rB & 63));
+                                if constexpr (!FULL) m &= LIVE[k];
+                                c[k] = m;
+                            }
+                            if (any(c)) {
+                                const int a1 = lowest(c);
+                                const int d1 = mr_of(a1);
+                                const V va1 = isA ? value_of_row(xa, a1) : value_of_row(xb, a1);
+                                const V vB = value_of_row(yb, a1);
+                                rematch(a1, fx, va1);
+                                rematch(rB, d1, vB);
+                                pending = 0;
+                            }
+                        }
+                        // re-matched cells that hold virtual bytes: what is left of their real bytes
+#pragma unroll
+                        for (int k = 0; k < NR; ++k) {
+                            if (chg[k] && vfl[k] != 0 && mr[k] >= 0) {
+                                const int d = mr[k];
+                                const i64 l = max(PR[k], PC[d]);
+                                const i64 h = min(ER[k], EC[d]);
+                                const i64 av = (h > l ? h - l : 0) + (d == lid[k] ? diag[k] : 0);
+                                rl[k] = (i64)rv[k] > av ? (RL)((i64)rv[k] - av) : (RL)0;
+                            }
+                        }
+                        if (pending == 1) {
+                            // the second row needs a longer path: the search takes it from here
+#pragma unroll
+                            for (int k = 0; k < NR; ++k) loaded[k] = mr[k];
+                            set_mr(rB, -1);
+#pragma unroll
+                            for (int w = 0; w < NR; ++w)
+                                if ((fx >> 6) == w) FREEC[w] |= 1ull << (fx & 63);
+                            masks_from_lds();
+                            if (!augment(rB)) status = -3;
+                        }
+                    }
                 }
-                masks_from_lds();
+                if (pending == 0) continue;     // LDS and the registers agree: on to the next stage
+                if (pending >= 2) {
+                    u64 z[NR];
 #pragma unroll
-                for (int k = 0; k < NR; ++k) mr[k] = zero[k] ? -1 : mr[k];
-                bool ok = true;
+                    for (int w = 0; w < NR; ++w) z[w] = Z[w];
+                    while (any(z)) {
+                        const int a = lowest(z);
+                        const int d = mr_of(a);
+                        const u64 bit = 1ull << (a & 63);
+                        clear_edge(a, d);
 #pragma unroll
-                for (int w = 0; w < NR; ++w)
-                    for (u64 zz = Z[w]; zz && ok; zz &= zz - 1) ok = augment(64 * w + __builtin_ctzll(zz));
-                if (!ok) status = -3;
+                        for (int k = 0; k < NR; ++k)
+                            if ((d >> 6) == k) FREEC[k] |= 1ull << (d & 63);
+#pragma unroll
+                        for (int w = 0; w < NR; ++w)
+                            if ((a >> 6) == w) z[w] &= ~bit;
+                    }
+                    masks_from_lds();
+#pragma unroll
+                    for (int k = 0; k < NR; ++k) mr[k] = zero[k] ? -1 : mr[k];
+                    bool ok = true;
+#pragma unroll
+                    for (int w = 0; w < NR; ++w)
+                        for (u64 zz = Z[w]; zz && ok; zz &= zz - 1) ok = augment(64 * w + __builtin_ctzll(zz));
+                    if (!ok) status = -3;
+                }
             }
             if (__builtin_expect(status < 0, 0)) break;     // a row is unmatched: nothing to sync
             sync_matched(std::false_type{});
