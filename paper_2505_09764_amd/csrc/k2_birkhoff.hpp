@@ -10,7 +10,7 @@
 // dependency on top of that.
 //   * a single wavefront owns the matrix, so no step needs a workgroup barrier;
 //     lane l owns rows l, l+64 and columns l, l+64 (S <= 128);
-//   * the residual matrix R = Q + A lives in LDS (int64 words, odd row stride so
+//   * the residual matrix R = Q + A lives in LDS (8-byte cells, odd row stride so
 //     that a column - one cell per lane - spreads over the banks).  The residual of
 //     each row's matched cell is also held in a register; after every subtraction
 //     the register is written back, so LDS is current for every cell;
@@ -37,18 +37,28 @@
 //   * the virtual matrix A of the embedding (Section 4.4 "Adapting an arbitrary
 //     matrix to a valid form") is never stored: pouring row deficits into column
 //     deficits in ascending order makes A[a][d] the overlap of two prefix-sum
-//     intervals (plus the diagonal term); cells that hold virtual bytes are
-//     flagged in the top bit of their LDS word and the overlap is recomputed only
-//     when such a cell gets matched;
-//   * no residual exceeds L, the largest row/column sum, so when L < 2^31 the matrix
-//     is repacked in place to 32-bit words and the stage loop runs on 32-bit
-//     registers; the real bytes left in a cell never exceed the largest entry of
-//     Q, so they are counted in 32 bits whenever that fits, even where virtual
-//     bytes push the residuals beyond 32 bits; when S fills the lane slots exactly
-//     (64 or 128) the stage loop carries no bounds predicates.  Predicated LDS
-//     writes and mid-loop exits cost a lone wavefront far more than their
-//     instruction count suggests, so the stage avoids them: unconditional
-//     write-back, the stage weight stored by every lane.
+//     intervals (plus the diagonal term);
+//   * no residual exceeds L, the largest row/column sum.  When L < 2^31 - directly, or
+//     after a power of two common to all entries has been divided out - a cell of R
+//     is two 32-bit halves, the residual and the real bytes left in it; the
+//     write-back stores both (one 64-bit store), the reads of the repair return both,
+//     and the stage loop runs on 32-bit registers with nothing to recompute when a
+//     cell that holds virtual bytes gets matched (on skewed traffic, where most of L
+//     is virtual, that is every third stage).  Otherwise a cell is one 64-bit word
+//     with the top bit set where it holds virtual bytes, and the overlap is
+//     recomputed when such a cell gets matched; the real bytes left in a cell never
+//     exceed the largest entry of Q, so they are counted in 32 bits whenever that
+//     fits;
+//   * when S fills the lane slots exactly (64 or 128) the stage loop carries no
+//     bounds predicates.  Predicated LDS writes and mid-loop exits cost a lone
+//     wavefront far more than their instruction count suggests, so the stage avoids
+//     them: unconditional write-back, the stage weight stored by every lane;
+//   * LDS instructions complete in order and the compiler's wait for the reads of
+//     the repair also waits for whatever was issued after them, so the atomic that
+//     clears the support bit is issued once the reads have been consumed, and only
+//     lane 0 sends it to the mask word (the other lanes to a word of their own): 64
+//     lanes on one word are 64 serial passes that the next stage's LDS traffic would
+//     queue behind.
 //
 // Canonical choices that make the result a function of the matrix alone (the
 // paper leaves them open): level-synchronous search from one unmatched row, the
@@ -82,10 +92,11 @@ __host__ __device__ inline size_t k2_lds_data_bytes(int S) {
 
 // ... plus a spare region that the lane slots without a row (S below 64 * NR) read and write
 // instead of a row of R, so that the stage loop needs no bounds predicate, plus the support
-// masks: one 128-bit row mask per column
+// masks: one 128-bit row mask per column, plus one word per lane for the lanes that take no
+// part in a mask update
 __host__ __device__ inline size_t k2_lds_spare_bytes(int S) { return (size_t)(S + 2) * 8; }
 inline size_t k2_lds_bytes(int S) {
-    return k2_lds_data_bytes(S) + k2_lds_spare_bytes(S) + (size_t)128 * 16;
+    return k2_lds_data_bytes(S) + k2_lds_spare_bytes(S) + (size_t)128 * 16 + 256;
 }
 
 // NR = rows (and columns) per lane: 1 for S <= 64, 2 for S <= 128.
@@ -107,12 +118,15 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     i64 diag[NR], PR[NR], ER[NR];
     i64 qmax = 0;
     int sh = 0;         // every byte count below is in units of 2^sh bytes (0 unless that makes L fit 31 bits)
-    const i64 L = embed_into_lds<NR>(wsQ, wsPart, b, S, RS, lane, R, PC, EC, diag, PR, ER, qmax, sh);
+    const i64 L = embed_into_lds<NR, true>(wsQ, wsPart, b, S, RS, lane, R, PC, EC, diag, PR, ER, qmax, sh);
     if (L <= 0) {
         if (lane == 0) out_num[b] = (int32_t)L;     // -1: invalid input, 0: nothing to send
         return;
     }
 
+    // Residuals never exceed L: when L < 2^31 the embedding has left cells of two 32-bit halves
+    // (residual, real bytes left) and the stage loop runs on 32-bit registers.
+    const bool narrow = L < ((i64)1 << 31);
     // support masks: bit a of cm[k][a/64] set while R[a][column lane+64k] > 0
     u64 cm[NR][NR];
 #pragma unroll
@@ -122,7 +136,8 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         for (int w = 0; w < NR; ++w) cm[k][w] = 0;
         if (x < S) {
             for (int a = 0; a < S; ++a) {
-                const u64 pos = (R[a * RS + x] & ~VFLAG) != 0;
+                const u64 w0 = R[a * RS + x];
+                const u64 pos = narrow ? (u32)w0 != 0 : (w0 & ~VFLAG) != 0;
 #pragma unroll
                 for (int w = 0; w < NR; ++w)
                     if ((a >> 6) == w) cm[k][w] |= pos << (a & 63);
@@ -133,15 +148,17 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     // Residuals never exceed L, so when L < 2^31 the whole stage loop runs on 32-bit words: the
     // residual matrix is repacked in place (flag in bit 31) and every per-stage subtraction,
     // comparison and select is one instruction instead of two.
-    const bool narrow = L < ((i64)1 << 31);
-    if (narrow) repack_narrow(R, S * RS, lane);
-    auto run = [&](auto tag, auto rltag) {
+    auto run = [&](auto tag, auto rltag, auto pairtag) {
         typedef decltype(tag) V;                // word type of the residuals
         typedef std::make_signed_t<V> SV;
         typedef decltype(rltag) RL;             // signed type of the real bytes left in a cell
         constexpr i64 RL_MAX = (i64)std::numeric_limits<RL>::max();
         constexpr V VF = (V)((V)1 << (sizeof(V) * 8 - 1));   // the cell holds virtual bytes
-        V* Rv = reinterpret_cast<V*>(k2_smem);
+        // PAIRS: a cell of R is {low: residual, high: real bytes left}, kept current by the
+        // write-back; otherwise one word, top bit set where the cell holds virtual bytes
+        constexpr bool PAIRS = decltype(pairtag)::value;
+        typedef std::conditional_t<PAIRS, u64, V> CELL;
+        CELL* Rv = reinterpret_cast<CELL*>(k2_smem);
         auto wave_min = [&](V v) -> V {
             if constexpr (sizeof(V) == 4) return wave_min_u32(v);
             else return wave_min_u64(v);
@@ -153,19 +170,32 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             lid[k] = lane + 64 * k;
             // a slot without a row keeps mr = loaded = -1: base + (-1) is its spare word
             // (the first reload, before any row is loaded, reads base + 0: the next spare word)
-            const u32 spare = (u32)(k2_lds_data_bytes(S) / sizeof(V)) + 1u;
+            const u32 spare = (u32)(k2_lds_data_bytes(S) / sizeof(CELL)) + 1u;
             rowbase[k] = lane + 64 * k < S ? (u32)(lane + 64 * k) * (u32)RS : spare;
         }
         int mr[NR], loaded[NR];
         SV rv[NR];
         RL rl[NR];
         u32 vfl[NR];       // bit 31: the matched cell holds virtual bytes (the flag of its LDS word)
+        auto val_of = [&](CELL x) -> V {
+            if constexpr (PAIRS) return (V)(u32)x;
+            else return x & (V)~VF;
+        };
+        auto real_of = [&](CELL x) -> RL {      // where the cell holds no virtual bytes
+            if constexpr (PAIRS) return (RL)(u32)(x >> 32);
+            else return (RL)(x & (V)~VF);
+        };
         auto with_flag = [&](SV v, u32 fl) -> V {
             if constexpr (sizeof(V) == 8) return (V)v | ((V)fl << 32);
             else return (V)v | fl;
         };
-        auto flag_of = [&](V x) -> u32 {
-            if constexpr (sizeof(V) == 8) return (u32)(x >> 32) & 0x80000000u;
+        auto cell_of = [&](SV v, RL real, u32 fl) -> CELL {
+            if constexpr (PAIRS) return (u64)(u32)v | ((u64)(u32)real << 32);
+            else return with_flag(v, fl);
+        };
+        auto flag_of = [&](CELL x) -> u32 {
+            if constexpr (PAIRS) return 0u;
+            else if constexpr (sizeof(V) == 8) return (u32)(x >> 32) & 0x80000000u;
             else return (u32)x & 0x80000000u;
         };
 #pragma unroll
@@ -216,26 +246,26 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         auto sync_matched = [&](auto first_tag) {
             constexpr bool FIRST = decltype(first_tag)::value;
             constexpr bool PLAIN = !FIRST;
-            V x[NR];
+            CELL x[NR];
             bool ch[NR];
 #pragma unroll
             for (int k = 0; k < NR; ++k) {
                 ch[k] = mr[k] != loaded[k];
                 if constexpr (PLAIN) {
-                    Rv[rowbase[k] + (u32)loaded[k]] = with_flag(rv[k], vfl[k]);
+                    Rv[rowbase[k] + (u32)loaded[k]] = cell_of(rv[k], rl[k], vfl[k]);
                     x[k] = Rv[rowbase[k] + (u32)mr[k]];
                 } else {
-                    if (ch[k] && rv[k] > 0) Rv[rowbase[k] + (u32)loaded[k]] = with_flag(rv[k], vfl[k]);
+                    if (ch[k] && rv[k] > 0) Rv[rowbase[k] + (u32)loaded[k]] = cell_of(rv[k], rl[k], vfl[k]);
                     x[k] = Rv[rowbase[k] + (u32)max(mr[k], 0)];
                 }
             }
             u64 anyv = 0;
 #pragma unroll
             for (int k = 0; k < NR; ++k) {
-                const V val = x[k] & (V)~VF;
+                const V val = val_of(x[k]);
                 const u32 fl = flag_of(x[k]);
                 rv[k] = ch[k] ? (SV)val : rv[k];
-                rl[k] = ch[k] ? (RL)val : rl[k];
+                rl[k] = ch[k] ? real_of(x[k]) : rl[k];
                 anyv |= ballot(ch[k]) & ballot(fl != 0);
                 vfl[k] = ch[k] ? fl : vfl[k];
                 loaded[k] = mr[k];
@@ -332,9 +362,13 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         // cell (a, d) has left the support (a, d wave-uniform): one LDS atomic that nothing waits
         // for; every lane sends the same AND to the same word (written as an instruction of its
         // own: the compiler would wrap an atomicAnd into a dozen instructions that pick one lane)
+        const u32 dummy_addr = (u32)(k2_lds_data_bytes(S) + k2_lds_spare_bytes(S)) + 128u * 16u + (u32)lane * 4u;
         auto clear_edge = [&](int a, int d) {
-            const u32 addr = (u32)(k2_lds_data_bytes(S) + k2_lds_spare_bytes(S)) +
+            // lane 0 clears the bit; the other lanes send theirs to a word of their own behind the
+            // masks (64 lanes on one word would be 64 serial passes through the LDS pipeline)
+            const u32 real = (u32)(k2_lds_data_bytes(S) + k2_lds_spare_bytes(S)) +
                              (u32)d * 16u + (u32)(a >> 5) * 4u;
+            const u32 addr = lane == 0 ? real : dummy_addr;
             const u32 keep = ~(1u << (a & 31));
             asm volatile("ds_and_b32 %0, %1" : : "v"(addr), "v"(keep) : "memory");
         };
@@ -345,33 +379,33 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         constexpr bool LATE_WRITE_BACK = NR == 1;
         auto write_back = [&]() {
 #pragma unroll
-            for (int k = 0; k < NR; ++k) Rv[rowbase[k] + (u32)mr[k]] = with_flag(rv[k], vfl[k]);
+            for (int k = 0; k < NR; ++k) Rv[rowbase[k] + (u32)mr[k]] = cell_of(rv[k], rl[k], vfl[k]);
         };
         // x of the lane slot that holds row a (a wave-uniform), as a wave-uniform value
-        auto value_of_row = [&](const V (&x)[NR], int a) -> V {
+        auto value_of_row = [&](const CELL (&x)[NR], int a) -> CELL {
             if constexpr (NR == 2) {
-                if constexpr (sizeof(V) == 8) {
+                if constexpr (sizeof(CELL) == 8) {
                     const u64 b0 = rdl64((u64)x[0], a & 63), b1 = rdl64((u64)x[1], a & 63);
-                    return (V)((a & 64) ? b1 : b0);
+                    return (CELL)((a & 64) ? b1 : b0);
                 } else {
                     const u32 b0 = rdl((u32)x[0], a & 63), b1 = rdl((u32)x[1], a & 63);
-                    return (V)((a & 64) ? b1 : b0);
+                    return (CELL)((a & 64) ? b1 : b0);
                 }
             } else {
-                if constexpr (sizeof(V) == 8) return (V)rdl64((u64)x[0], a);
-                else return (V)rdl((u32)x[0], a);
+                if constexpr (sizeof(CELL) == 8) return (CELL)rdl64((u64)x[0], a);
+                else return (CELL)rdl((u32)x[0], a);
             }
         };
         // a cell's word without its flag bit, folded to 32 bits: non-zero while the cell is positive
-        auto fold = [&](V x) -> u32 {
-            if constexpr (sizeof(V) == 8) return ((u32)((u64)x >> 32) & 0x7FFFFFFFu) | (u32)x;
+        auto fold = [&](CELL x) -> u32 {
+            if constexpr (PAIRS) return (u32)x;
+            else if constexpr (sizeof(V) == 8) return ((u32)((u64)x >> 32) & 0x7FFFFFFFu) | (u32)x;
             else return (u32)x & 0x7FFFFFFFu;
         };
         // Whether a three-level repair is worked out from the reads of the stage plus one more
         // column read, or on the support masks alone: measured, the first wins when a lane holds
         // two rows and loses when it holds one.
         constexpr bool DEEP_FROM_READS = NR == 2;
-        // two exhausted cells repaired on reads of R: measured, a gain only with two rows per lane
         constexpr bool PAIR_FROM_READS = NR == 2;
         enum { GO_ON = 0, DONE, GENERAL, DEEP };
         for (;;) {
@@ -381,7 +415,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
             u64 Z[NR];
             bool zero[NR];
             int r0 = 0, f = 0, nz = 0;
-            V ea[NR], eb[NR];      // R[row][f] and R[r0][column of the row], read by the stage that left
+            CELL ea[NR], eb[NR];      // R[row][f] and R[r0][column of the row], read by the stage that left
 #pragma unroll
             for (int k = 0; k < NR; ++k) ea[k] = eb[k] = 0;
             if (__builtin_expect(s >= max_stages, 0)) { status = -2; break; }
@@ -443,7 +477,6 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     eb[k] = Rv[(u32)r0 * (u32)RS + (u32)(FULL ? mr[k] : max(mr[k], 0))];
                 }
                 if constexpr (LATE_WRITE_BACK) write_back();
-                clear_edge(r0, f);
                 u64 c2[NR];
 #pragma unroll
                 for (int k = 0; k < NR; ++k) {
@@ -453,22 +486,32 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                         if ((r0 >> 6) == k) c2[k] &= ~(1ull << (r0 & 63));     // its cell (r0, f) was read stale
                     if constexpr (!FULL) c2[k] &= LIVE[k];
                 }
+                {   // issued once the reads have been consumed (the unused operand pins it behind
+                    // the candidate masks): nothing waits for it
+                    const u32 real = (u32)(k2_lds_data_bytes(S) + k2_lds_spare_bytes(S)) +
+                                     (u32)f * 16u + (u32)(r0 >> 5) * 4u;
+                    const u32 addr = lane == 0 ? real : dummy_addr;
+                    const u32 keep = ~(1u << (r0 & 31));
+                    u64 dep = c2[0];
+                    if constexpr (NR == 2) dep |= c2[1];
+                    asm volatile("ds_and_b32 %0, %1" : : "v"(addr), "v"(keep), "s"(dep) : "memory");
+                }
                 if (__builtin_expect(!any(c2), 0)) { why = DEEP; break; }
                 const int a1 = lowest(c2);
                 const int d1 = mr_of(a1);
-                const V vb = value_of_row(eb, a1);
+                const CELL vb = value_of_row(eb, a1);
                 u64 anyv = 0;
 #pragma unroll
                 for (int k = 0; k < NR; ++k) {
                     const bool isA = lid[k] == a1, isR = lid[k] == r0;
-                    const V x = isA ? ea[k] : vb;
+                    const CELL x = isA ? ea[k] : vb;
                     const bool ch = isA || isR;
-                    const V val = x & (V)~VF;
+                    const V val = val_of(x);
                     const u32 fl = flag_of(x);
                     rv[k] = ch ? (SV)val : rv[k];
-                    rl[k] = ch ? (RL)val : rl[k];
+                    rl[k] = ch ? real_of(x) : rl[k];
                     vfl[k] = ch ? fl : vfl[k];
-                    anyv |= (ballot(isA) | ballot(isR)) & ballot((SV)x < 0);
+                    anyv |= (ballot(isA) | ballot(isR)) & ballot(flag_of(x) != 0);
                     mr[k] = isA ? f : (isR ? d1 : mr[k]);
                 }
                 if (__builtin_expect(anyv != 0, 0)) {
@@ -516,7 +559,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                         if (any(c3)) {
                             const int a2 = lowest(c3);
                             const int d2 = mr_of(a2);
-                            V ec[NR];
+                            CELL ec[NR];
                             u64 c1[NR];
 #pragma unroll
                             for (int k = 0; k < NR; ++k) {
@@ -526,17 +569,17 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                             if (any(c1)) {
                                 const int a1 = lowest(c1);
                                 const int d1 = mr_of(a1);
-                                const V vb = value_of_row(eb, a1);
+                                const CELL vb = value_of_row(eb, a1);
                                 u64 anyv = 0;
 #pragma unroll
                                 for (int k = 0; k < NR; ++k) {
                                     const bool isA2 = lid[k] == a2, isA1 = lid[k] == a1, isR = lid[k] == r0;
-                                    const V x = isA2 ? ea[k] : (isA1 ? ec[k] : vb);
+                                    const CELL x = isA2 ? ea[k] : (isA1 ? ec[k] : vb);
                                     const bool ch = isA2 || isA1 || isR;
-                                    const V val = x & (V)~VF;
+                                    const V val = val_of(x);
                                     const u32 fl = flag_of(x);
                                     rv[k] = ch ? (SV)val : rv[k];
-                                    rl[k] = ch ? (RL)val : rl[k];
+                                    rl[k] = ch ? real_of(x) : rl[k];
                                     vfl[k] = ch ? fl : vfl[k];
                                     anyv |= ballot(ch && fl != 0);
                                     mr[k] = isA2 ? f : (isA1 ? d2 : (isR ? d1 : mr[k]));
@@ -634,7 +677,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     if constexpr (LATE_WRITE_BACK) write_back();
                     clear_edge(rA, fA);
                     clear_edge(rB, fB);
-                    V xa[NR], xb[NR], ya[NR];       // columns fA, fB; row rA along the matching
+                    CELL xa[NR], xb[NR], ya[NR];       // columns fA, fB; row rA along the matching
                     u64 others[NR];                 // rows that hold a matched cell
 #pragma unroll
                     for (int k = 0; k < NR; ++k) {
@@ -648,21 +691,21 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 #pragma unroll
                     for (int k = 0; k < NR; ++k) chg[k] = false;
                     // row `row` (wave-uniform) is matched to column `col`, whose word in R is x
-                    auto rematch = [&](int row, int col, V x) {
-                        const V val = x & (V)~VF;
+                    auto rematch = [&](int row, int col, CELL x) {
+                        const V val = val_of(x);
                         const u32 fl = flag_of(x);
 #pragma unroll
                         for (int k = 0; k < NR; ++k) {
                             const bool me = lid[k] == row;
                             rv[k] = me ? (SV)val : rv[k];
-                            rl[k] = me ? (RL)val : rl[k];
+                            rl[k] = me ? real_of(x) : rl[k];
                             vfl[k] = me ? fl : vfl[k];
                             mr[k] = me ? col : mr[k];
                             chg[k] = chg[k] || me;
                         }
                     };
                     int fx = -1;                    // the column still free after the first row
-                    const V yAB = value_of_row(ya, rB);     // R[rA][fB]: rB's register still names fB
+                    const CELL yAB = value_of_row(ya, rB);     // R[rA][fB]: rB's register still names fB
                     if (fold(yAB) != 0) {
                         rematch(rA, fB, yAB);
                         fx = fA;
@@ -678,11 +721,11 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                         if (ra || rb) {
                             const bool takeA = ra && (!rb || fA < fB);      // the lower free column
                             int a1;
-                            V va1;
+                            CELL va1;
                             if (takeA) { a1 = lowest(ca); va1 = value_of_row(xa, a1); }
                             else { a1 = lowest(cb); va1 = value_of_row(xb, a1); }
                             const int d1 = mr_of(a1);
-                            const V vA = value_of_row(ya, a1);
+                            const CELL vA = value_of_row(ya, a1);
                             rematch(a1, takeA ? fA : fB, va1);
                             rematch(rA, d1, vA);
                             fx = takeA ? fB : fA;
@@ -691,17 +734,17 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     if (fx >= 0) {
                         pending = 1;
                         const bool isA = fx == fA;
-                        const V xB = isA ? value_of_row(xa, rB) : value_of_row(xb, rB);     // R[rB][fx]
+                        const CELL xB = isA ? value_of_row(xa, rB) : value_of_row(xb, rB);     // R[rB][fx]
                         if (fold(xB) != 0) {
                             rematch(rB, fx, xB);
                             pending = 0;
                         } else {
-                            V yb[NR];               // row rB along the matching as it is now
+                            CELL yb[NR];               // row rB along the matching as it is now
                             u64 c[NR];
 #pragma unroll
                             for (int k = 0; k < NR; ++k) {
                                 yb[k] = Rv[(u32)rB * (u32)RS + (u32)(FULL ? mr[k] : max(mr[k], 0))];
-                                const V xk = isA ? xa[k] : xb[k];
+                                const CELL xk = isA ? xa[k] : xb[k];
                                 u64 m = ballot(min(fold(yb[k]), fold(xk)) != 0);
                                 if ((rB >> 6) == k) m &= ~(1ull << (rB & 63));
                                 if constexpr (!FULL) m &= LIVE[k];
@@ -710,8 +753,8 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                             if (any(c)) {
                                 const int a1 = lowest(c);
                                 const int d1 = mr_of(a1);
-                                const V va1 = isA ? value_of_row(xa, a1) : value_of_row(xb, a1);
-                                const V vB = value_of_row(yb, a1);
+                                const CELL va1 = isA ? value_of_row(xa, a1) : value_of_row(xb, a1);
+                                const CELL vB = value_of_row(yb, a1);
                                 rematch(a1, fx, va1);
                                 rematch(rB, d1, vB);
                                 pending = 0;
@@ -775,9 +818,9 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     };
     // the real bytes of a cell never exceed the largest entry of Q: 32-bit counters when that
     // fits, whatever the virtual bytes make of the residuals
-    if (narrow) run((u32)0, (int32_t)0);
-    else if (qmax < ((i64)1 << 31)) run((u64)0, (int32_t)0);
-    else run((u64)0, (i64)0);
+    if (narrow) run((u32)0, (int32_t)0, std::true_type{});
+    else if (qmax < ((i64)1 << 31)) run((u64)0, (int32_t)0, std::false_type{});
+    else run((u64)0, (i64)0, std::false_type{});
 }
 
 // One wavefront per matrix: matrix blockIdx.x.  COST: the same wavefront goes on to evaluate the

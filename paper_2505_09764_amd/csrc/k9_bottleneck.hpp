@@ -81,7 +81,7 @@ k9_bottleneck(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
     }
     const bool narrow = L < ((i64)1 << 31);
     if (narrow) {
-        repack_narrow<false>(R, S * S, lane);
+        repack_narrow(R, S * S, lane);
     } else {
         for (int e = lane; e < S * S; e += 64) R[e] &= ~VFLAG;
         wave_sync();

@@ -141,6 +141,9 @@ __device__ __forceinline__ void column_mask(const u64 (&cm)[NR][NR], int d, u64 
 // diagonal - and leaves R = Q + A in LDS, bit 63 set where a cell holds virtual bytes.  PR, ER,
 // diag stay in registers (per row of the lane), PC, EC go to LDS.  qmax receives the largest
 // entry of Q (no cell ever holds more real bytes than that).
+// PAIRS: when L < 2^31 a cell is left as two 32-bit halves instead - low: the residual Q + A,
+// high: the real bytes Q - without a flag, so that whoever matches the cell reads both counts
+// at once and never has to recompute the overlap.
 // Common factor: when L does not fit 31 bits but every entry of Q is a multiple of 2^sh and
 // L / 2^sh does, the whole matrix is divided by 2^sh (sh is returned; 0 otherwise).  Sums,
 // deficits and virtual bytes are multiples of 2^sh as well, the decomposition of the divided
@@ -149,7 +152,7 @@ __device__ __forceinline__ void column_mask(const u64 (&cm)[NR][NR], int d, u64 
 // whole tokens is of that kind: every entry a multiple of the token size.
 // Returns -1 if kernel 1 flagged the matrix as invalid, else L (0: nothing to send), divided
 // by 2^sh like everything else.
-template <int NR>
+template <int NR, bool PAIRS = false>
 __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
                                               const i64* __restrict__ wsPart, int b, int S, int RS,
                                               int lane, u64* R, i64* PC, i64* EC,
@@ -245,19 +248,26 @@ __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
             base_c += __shfl(ic, 63, 64);
         }
     }
+    // PAIRS and L < 2^31: every word becomes {low half: residual, high half: real bytes}; the
+    // virtual bytes are added to the low half only (the sum stays below 2^31: no carry) and no
+    // flag is set
+    const bool pairs = PAIRS && L < ((i64)1 << 31);
+    const u64 vflag = pairs ? 0ull : VFLAG;
+    if (pairs)
+        for (int e = lane; e < S * RS; e += 64) R[e] |= R[e] << 32;
     wave_sync();
 #pragma unroll
     for (int k = 0; k < NR; ++k) {
         const int x = lane + 64 * k;
         if (x < S) {
-            if (diag[k] > 0) R[x * RS + x] = (R[x * RS + x] + (u64)diag[k]) | VFLAG;
+            if (diag[k] > 0) R[x * RS + x] = (R[x * RS + x] + (u64)diag[k]) | vflag;
             if (ER[k] > PR[k]) {
                 for (int j = 0; j < S; ++j) {
                     int d = j + x;
                     d = d >= S ? d - S : d;
                     const i64 l = max(PR[k], PC[d]);
                     const i64 h = min(ER[k], EC[d]);
-                    if (h > l) R[x * RS + d] = (R[x * RS + d] + (u64)(h - l)) | VFLAG;
+                    if (h > l) R[x * RS + d] = (R[x * RS + d] + (u64)(h - l)) | vflag;
                 }
             }
         }
@@ -266,9 +276,8 @@ __device__ __forceinline__ i64 embed_into_lds(const i64* __restrict__ wsQ,
     return L;
 }
 
-// No residual exceeds L, the largest line sum: when L < 2^31 the n 64-bit words of R (flag in
-// bit 63) are repacked in place to 32-bit words (flag in bit 31, or dropped).
-template <bool KEEP_FLAG = true>
+// No residual exceeds L, the largest line sum: when L < 2^31 the n 64-bit words of R are
+// repacked in place to 32-bit words (the flag in bit 63 is dropped).
 __device__ __forceinline__ void repack_narrow(u64* R, int n, int lane) {
     u32* R32 = reinterpret_cast<u32*>(R);
     for (int e0 = 0; e0 < n; e0 += 64) {
@@ -276,7 +285,7 @@ __device__ __forceinline__ void repack_narrow(u64* R, int n, int lane) {
         u64 v = 0;
         if (e < n) v = R[e];
         wave_sync();                    // chunk read before its (lower) words are rewritten
-        if (e < n) R32[e] = (u32)v | ((KEEP_FLAG && (v & VFLAG)) ? 0x80000000u : 0u);
+        if (e < n) R32[e] = (u32)v;
     }
     wave_sync();
 }
