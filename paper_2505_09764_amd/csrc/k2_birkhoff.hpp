@@ -320,10 +320,11 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         int32_t* stg = out_stages + (size_t)b * max_stages * S;
         i64* byt = out_bytes + (size_t)b * max_stages * S;
         i64* cw = wsC + (size_t)b * max_stages;
-        i64 Lrem = L;
+        std::conditional_t<PAIRS, u32, i64> Lrem = (std::conditional_t<PAIRS, u32, i64>)L;
         int s = 0;
         // byte offsets of the lane's first slot in the stage row being written
         u32 soff = (u32)lane * 4u, boff = (u32)lane * 8u, coff = 0;
+        asm volatile("" : "+v"(coff));     // a vector register of its own: the store needs one anyway
         // mr of a uniform row
         auto mr_of = [&](int a) -> int {
             if constexpr (NR == 2) {
@@ -453,12 +454,12 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     Z[k] = ballot(zero[k]);
                 }
                 // every lane stores the same word: no divergent branch on the path
-                *reinterpret_cast<i64*>(reinterpret_cast<char*>(cw) + coff) = (i64)c << sh;
+                *reinterpret_cast<i64*>(reinterpret_cast<char*>(cw) + coff) = (i64)(std::make_unsigned_t<SV>)c << sh;
                 ++s;
                 soff += 4u * (u32)S;
                 boff += 8u * (u32)S;
                 coff += 8u;
-                Lrem -= c64;
+                Lrem -= (std::conditional_t<PAIRS, u32, i64>)c64;
                 if (__builtin_expect(Lrem == 0, 0)) { why = DONE; break; }
                 if constexpr (!LATE_WRITE_BACK) write_back();
                 nz = 0;
@@ -469,8 +470,14 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 // takes the lowest row a1 that has a positive cell in column f and whose column
                 // d1 has a positive cell in row r0: both tests are reads of R, and the two cells
                 // read by a1's lane are the ones that get matched.
-                r0 = lowest(Z);
-                f = mr_of(r0);
+                if constexpr (NR == 2) {
+                    const int ln = __builtin_ctzll(Z[0] | Z[1]);
+                    r0 = ln | (Z[0] ? 0 : 64);
+                    f = (int)rdl((u32)(zero[0] ? mr[0] : mr[1]), ln);
+                } else {
+                    r0 = lowest(Z);
+                    f = mr_of(r0);
+                }
 #pragma unroll
                 for (int k = 0; k < NR; ++k) {
                     ea[k] = Rv[rowbase[k] + (u32)f];
@@ -498,8 +505,17 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 }
                 if (__builtin_expect(!any(c2), 0)) { why = DEEP; break; }
                 const int a1 = lowest(c2);
-                const int d1 = mr_of(a1);
-                const CELL vb = value_of_row(eb, a1);
+                int d1;
+                CELL vb;
+                if constexpr (NR == 2) {
+                    // pick the slot first, then one readlane per word
+                    const bool up = c2[0] == 0;
+                    d1 = (int)rdl((u32)(up ? mr[1] : mr[0]), a1 & 63);
+                    vb = (CELL)rdl64((u64)(up ? eb[1] : eb[0]), a1 & 63);
+                } else {
+                    d1 = mr_of(a1);
+                    vb = value_of_row(eb, a1);
+                }
                 u64 anyv = 0;
 #pragma unroll
                 for (int k = 0; k < NR; ++k) {
