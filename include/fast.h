@@ -272,8 +272,8 @@ int fast_stage_offsets_batched(fast_plan_t *plan, int B, const int32_t *stages,
  *   out_redis_bytes    device, [B][max_stages] int64; [b][s] = largest, over the GPUs of all
  *                      servers that receive in stage s, of max(bytes the GPU forwards to other
  *                      GPUs of its server, bytes other GPUs forward to it); entries s >= K are 0
- * Enqueued on `stream`, asynchronous; uses its own part of the plan's workspace
- * (16 * S * (max_stages + 1) + 8 * S * S bytes per matrix).
+ * Enqueued on `stream`, asynchronous; uses its own part of the plan's workspace (4 * S bytes
+ * per matrix: one flag per source server), allocated at the first call and whenever B grows.
  */
 int fast_redistribution_batched(fast_plan_t *plan, int B, const int64_t *traffic,
                                 const int64_t *rebalance, const int32_t *stages,

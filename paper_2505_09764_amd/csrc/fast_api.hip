@@ -50,10 +50,7 @@ struct fast_plan {
     int32_t* soIdx;        // [B][P]
     // workspace of the redistribution analysis for `rd_cap_B` matrices
     int rd_cap_B;
-    int32_t* rdStart;      // [B][S][S] start of the pair's list within its source server's row
-    int32_t* rdCnt;        // [B][S][S] stages in which the pair occurs
-    fastk::i64x2* rdList;  // [B][S][max_stages + 1] (bytes per lane, stage) per (stage, source) that sends,
-                           //                    grouped by destination, in execution order
+    int32_t* rdNeed;       // [B][S] 1 where a source server's tiles need 64-bit intervals
     int last_B;            // B of the most recent synthesis call (0 = none)
     unsigned char* scratch_ptr;   // device address of `scratch` on the plan's device
     // timing: four events per recorded call
@@ -168,18 +165,13 @@ void launch_k1(const fast_plan* p, const synth_workspace& ws, int B, const i64* 
 }
 
 
-// The stage-walk kernel: with or without pair lists, with or without a stage order, and the
-// variant without store predicates when S is a multiple of its 64 source servers per wavefront.
-typedef void (*rd_offsets_fn)(const int32_t*, const i64*, const int32_t*, const int32_t*, i64*, int32_t*,
-                              int32_t*, fastk::i64x2*, int, int);
-rd_offsets_fn rd_offsets_kernel(int S, bool lists, bool ordered) {
+// The stage-walk kernel: with or without a stage order, and the variant without store predicates
+// when S is a multiple of its 64 source servers per wavefront.
+typedef void (*rd_offsets_fn)(const int32_t*, const i64*, const int32_t*, const int32_t*, i64*, int, int);
+rd_offsets_fn rd_offsets_kernel(int S, bool ordered) {
     const bool all = S % fastk::RD_ROWS == 0;
-    if (lists) {
-        if (ordered) return all ? &fastk::rd_offsets<true, true, true> : &fastk::rd_offsets<true, true, false>;
-        return all ? &fastk::rd_offsets<true, false, true> : &fastk::rd_offsets<true, false, false>;
-    }
-    if (ordered) return all ? &fastk::rd_offsets<false, true, true> : &fastk::rd_offsets<false, true, false>;
-    return all ? &fastk::rd_offsets<false, false, true> : &fastk::rd_offsets<false, false, false>;
+    if (ordered) return all ? &fastk::rd_offsets<true, true> : &fastk::rd_offsets<true, false>;
+    return all ? &fastk::rd_offsets<false, true> : &fastk::rd_offsets<false, false>;
 }
 
 // Device address of `scratch` on device `dev`, which has to be the current device; looked up
@@ -305,8 +297,7 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     p->soKeys = nullptr;
     p->soIdx = nullptr;
     p->rd_cap_B = 0;
-    p->rdStart = p->rdCnt = nullptr;
-    p->rdList = nullptr;
+    p->rdNeed = nullptr;
     p->last_B = 0;
     p->scratch_ptr = nullptr;
     p->timing = 0;
@@ -322,12 +313,20 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::k3_cost),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)(next_pow2(p->max_stages) * sizeof(i64)));
-    if (e == hipSuccess && fastk::rd_offsets_lds_bytes(S, true) > 48 * 1024) {
-        for (int k = 0; k < 4 && e == hipSuccess; ++k)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(rd_offsets_kernel(S, k < 2, k % 2 == 0)),
+    if (e == hipSuccess && fastk::rd_offsets_lds_bytes(S) > 48 * 1024) {
+        for (int k = 0; k < 2 && e == hipSuccess; ++k)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(rd_offsets_kernel(S, k == 0)),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)fastk::rd_offsets_lds_bytes(S, k < 2));
+                                    (int)fastk::rd_offsets_lds_bytes(S));
     }
+    if (e == hipSuccess && fastk::rd_volumes_lds_bytes<int>(S) > 48 * 1024)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::rd_volumes32),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)fastk::rd_volumes_lds_bytes<int>(S));
+    if (e == hipSuccess && fastk::rd_volumes_lds_bytes<i64>(S) > 48 * 1024)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::rd_volumes64),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)fastk::rd_volumes_lds_bytes<i64>(S));
     if (e != hipSuccess) {
         (void)hipGetLastError();
         delete p;
@@ -512,11 +511,10 @@ int fast_stage_offsets_batched(fast_plan_t* p, int B, const int32_t* stages,
     if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
     if (const int rc = check_device(p); rc != FAST_OK) return rc;
     const dim3 grid((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS, B);
-    auto kern = rd_offsets_kernel(p->S, false, stage_order != nullptr);
-    hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S, false),
+    auto kern = rd_offsets_kernel(p->S, stage_order != nullptr);
+    hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S),
                        stream, stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
-                       stage_order, reinterpret_cast<i64*>(out_stage_offset), nullptr, nullptr,
-                       nullptr, p->S, p->max_stages);
+                       stage_order, reinterpret_cast<i64*>(out_stage_offset), p->S, p->max_stages);
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     return FAST_OK;
 }
@@ -533,21 +531,16 @@ int fast_redistribution_batched(fast_plan_t* p, int B, const int64_t* traffic,
         return FAST_ERR_INVALID_ARG;
     if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
     if (const int rc = check_device(p); rc != FAST_OK) return rc;
-    const size_t S = p->S, M = p->max_stages;
+    const size_t M = p->max_stages;
     if (B > p->rd_cap_B) {
-        if (p->rdList) (void)hipFree(p->rdList);
-        p->rdList = nullptr;
+        if (p->rdNeed) (void)hipFree(p->rdNeed);
+        p->rdNeed = nullptr;
         p->rd_cap_B = 0;
-        const size_t nPair = (size_t)B * S * S, nList = (size_t)B * S * (M + 1);
-        unsigned char* base = nullptr;
-        if (hipMalloc(&base, nList * sizeof(fastk::i64x2) + 2 * nPair * sizeof(int32_t)) !=
-            hipSuccess) {
+        if (hipMalloc(&p->rdNeed, (size_t)B * p->S * sizeof(int32_t)) != hipSuccess) {
             (void)hipGetLastError();
+            p->rdNeed = nullptr;
             return FAST_ERR_OOM;
         }
-        p->rdList = reinterpret_cast<fastk::i64x2*>(base);     // 16-byte entries first: aligned
-        p->rdStart = reinterpret_cast<int32_t*>(p->rdList + nList);
-        p->rdCnt = p->rdStart + nPair;
         p->rd_cap_B = B;
     }
     const size_t nR = (size_t)B * M;
@@ -556,15 +549,25 @@ int fast_redistribution_batched(fast_plan_t* p, int B, const int64_t* traffic,
                                                                               : 2048)),
                        dim3(256), 0, stream, redis, nR);
     const dim3 grid((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS, B);
-    auto kern = rd_offsets_kernel(p->S, true, stage_order != nullptr);
-    hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S, true),
+    auto kern = rd_offsets_kernel(p->S, stage_order != nullptr);
+    hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S),
                        stream, stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
-                       stage_order, reinterpret_cast<i64*>(out_stage_offset), p->rdStart, p->rdCnt,
-                       p->rdList, p->S, p->max_stages);
-    hipLaunchKernelGGL(fastk::rd_volumes, dim3(p->S * p->S, B), dim3(64), 0, stream,
+                       stage_order, reinterpret_cast<i64*>(out_stage_offset), p->S, p->max_stages);
+    // the volumes read the offsets just written (same stream): 32-bit intervals wherever a source
+    // server's tiles allow it, the 64-bit kernel picks up the rest
+    const int items = B * p->S;
+    hipLaunchKernelGGL(fastk::rd_volumes32, dim3(fastk::rv_grid(items)), dim3(fastk::RV_THREADS32),
+                       fastk::rd_volumes_lds_bytes<int>(p->S), stream,
                        reinterpret_cast<const i64*>(traffic), reinterpret_cast<const i64*>(rebalance),
-                       num_stages, p->rdStart, p->rdCnt, p->rdList, redis, p->S, p->G,
-                       p->max_stages);
+                       stages, reinterpret_cast<const i64*>(stage_bytes),
+                       reinterpret_cast<const i64*>(out_stage_offset), num_stages, p->rdNeed, redis,
+                       B, p->S, p->G, p->max_stages);
+    hipLaunchKernelGGL(fastk::rd_volumes64, dim3((unsigned)(items < 256 ? items : 256)),
+                       dim3(fastk::RV_THREADS64), fastk::rd_volumes_lds_bytes<i64>(p->S), stream,
+                       reinterpret_cast<const i64*>(traffic), reinterpret_cast<const i64*>(rebalance),
+                       stages, reinterpret_cast<const i64*>(stage_bytes),
+                       reinterpret_cast<const i64*>(out_stage_offset), num_stages, p->rdNeed, redis,
+                       B, p->S, p->G, p->max_stages);
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     return FAST_OK;
 }
@@ -657,7 +660,7 @@ void fast_plan_destroy(fast_plan_t* p) {
     free_workspace(p);
     free_spo_workspace(p);
     if (p->soKeys) (void)hipFree(p->soKeys);
-    if (p->rdList) (void)hipFree(p->rdList);
+    if (p->rdNeed) (void)hipFree(p->rdNeed);
     if (p->ev) {
         for (int c = 0; c < FAST_MAX_TIMED_CALLS; ++c)
             for (int k = 0; k < 4; ++k)

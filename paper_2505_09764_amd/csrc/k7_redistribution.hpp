@@ -24,12 +24,16 @@
 //
 // rd_offsets   one thread per source server walks the stages in execution order
 //              keeping the bytes already sent to every destination in LDS: the
-//              per-stage send offsets; optionally also files every (stage, source)
-//              under its server pair (count, scan, fill - all in LDS), so that
-// rd_volumes   one wavefront per server pair builds the pair's 8 x 8 x 8 intervals
-//              once (lane (k, j) keeps its 8 in registers) and then runs through
-//              the pair's stages: overlap, row and column sums without the diagonal
-//              by DPP, wave maximum, atomic max into the stage's scale-up volume;
+//              per-stage send offsets;
+// rd_volumes   one workgroup per (matrix, source server) keeps, for all S destination
+//              servers, the prefix sums of the pair's lane-routing tile and traffic tile
+//              in LDS (everything the intervals above are made of), then runs through the
+//              stages of its source server: with the send offsets known every (stage,
+//              source) is independent of the others, so eight lanes - one per lane k of
+//              the destination - work out what the stage's chunk of lane k's queue holds
+//              for every GPU j, sums over the eight give what each GPU receives, the
+//              largest of forwarded and received goes to the stage's scale-up volume
+//              with an atomic max.  No lists, no workspace beyond one flag per source;
 // rd_matrices  one wavefront per (selected stage, source server) writes the whole
 //              G x G matrix.
 #pragma once
@@ -43,9 +47,7 @@ namespace fastk {
 constexpr int RD_ROWS = 64;     // source servers per workgroup of rd_offsets (one wavefront)
 constexpr int RD_UNROLL = 16;   // stages per batch of the pipelined walk
 
-inline size_t rd_offsets_lds_bytes(int S, bool lists) {
-    return (size_t)RD_ROWS * S * (lists ? sizeof(i64) + sizeof(int32_t) : sizeof(i64));
-}
+inline size_t rd_offsets_lds_bytes(int S) { return (size_t)RD_ROWS * S * sizeof(i64); }
 
 __global__ void __launch_bounds__(256) rd_zero(u64* __restrict__ p, size_t n) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
@@ -60,14 +62,11 @@ __global__ void __launch_bounds__(256) rd_zero(u64* __restrict__ p, size_t n) {
 // of RD_UNROLL stages is processed, the rows of batch n+1 and the indices of batch n+2
 // are in flight.
 // ALL: S is a multiple of RD_ROWS, every lane owns a real source server (no store predicate).
-// The pair lists have max_stages + 1 slots per source server: slot max_stages is a dump for the
-// lanes that do not send in a stage, so that the list store needs no predicate either.
-template <bool LISTS, bool ORDERED, bool ALL>
+template <bool ORDERED, bool ALL>
 __global__ void __launch_bounds__(RD_ROWS)
 rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_bytes,
            const int32_t* __restrict__ num_stages, const int32_t* __restrict__ order,
-           i64* __restrict__ out_offset, int32_t* __restrict__ lstart, int32_t* __restrict__ lcnt,
-           i64x2* __restrict__ list, int S, int max_stages) {
+           i64* __restrict__ out_offset, int S, int max_stages) {
     extern __shared__ __align__(16) unsigned char rd_smem[];
     constexpr int U = RD_UNROLL;
     const int b = blockIdx.y;
@@ -76,60 +75,22 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
     const int K = min(num_stages[b], max_stages);     // a count beyond the capacity is not trusted
     if (K <= 0) return;
     i64* sent = reinterpret_cast<i64*>(rd_smem);                    // [d][lane]
-    int32_t* next = reinterpret_cast<int32_t*>(sent + (size_t)RD_ROWS * S);   // [d][lane]
     const bool live = ALL || a < S;
     const int ac = live ? a : S - 1;                                // clamped: loads stay in range
-    for (int d = 0; d < S; ++d) {
-        sent[d * RD_ROWS + lane] = 0;
-        if constexpr (LISTS) next[d * RD_ROWS + lane] = 0;
-    }
+    for (int d = 0; d < S; ++d) sent[d * RD_ROWS + lane] = 0;
     const int32_t* st = stages + (size_t)b * max_stages * S;
     const i64* by = stage_bytes + (size_t)b * max_stages * S;
     const int32_t* ord = ORDERED ? order + (size_t)b * max_stages : nullptr;
     i64* off_out = out_offset + (size_t)b * max_stages * S;
 
-    if constexpr (LISTS) {
-        // how often does a send to each d, then where does each pair's list start
-        for (int s0 = 0; s0 < K; s0 += 2 * U) {
-            int dd[2 * U];
-#pragma unroll
-            for (int u = 0; u < 2 * U; ++u)
-                dd[u] = s0 + u < K ? st[(size_t)(s0 + u) * S + ac] : -1;
-#pragma unroll
-            for (int u = 0; u < 2 * U; ++u)
-                if (dd[u] >= 0 && dd[u] < S) atomicAdd(&next[dd[u] * RD_ROWS + lane], 1);
-        }
-        if (live) {
-            int acc = 0;
-            for (int d = 0; d < S; ++d) {
-                const int c = next[d * RD_ROWS + lane];
-                lstart[((size_t)b * S + a) * S + d] = acc;
-                lcnt[((size_t)b * S + a) * S + d] = c;
-                next[d * RD_ROWS + lane] = acc;
-                acc += c;
-            }
-        }
-    }
-
-    const size_t lbase = ((size_t)b * S + ac) * (size_t)(max_stages + 1);
-    // one stage: running offset of the pair (a, d) in LDS, optional list entry, send offset out.
-    // Branch-free for an idle row (d < 0): it adds 0 to word 0 of the lane's column.  Lanes
-    // beyond S work on a copy of row S-1 in their own LDS column and store nothing.
+    // one stage: running offset of the pair (a, d) in LDS, send offset out.  Branch-free for
+    // an idle row (d < 0): it adds 0 to word 0 of the lane's column.  Lanes beyond S work on a
+    // copy of row S-1 in their own LDS column and store nothing.
     auto stage = [&](int s, int d, i64 len) {
         const bool sends = d >= 0 && d < S;
         const int w = (sends ? d : 0) * RD_ROWS + lane;
         const i64 before = (i64)atomicAdd(reinterpret_cast<u64*>(&sent[w]), (u64)(sends ? len : 0));
-        const i64 off = sends ? before : 0;
-        if constexpr (LISTS) {
-            const int pos = atomicAdd(&next[w], sends ? 1 : 0);
-            if (live && sends && pos < max_stages) {    // pos < max_stages for any permutation
-                i64x2 entry;
-                entry.x = len;
-                entry.y = s;
-                list[lbase + pos] = entry;
-            }
-        }
-        if (live) off_out[(size_t)s * S + a] = off;
+        if (live) off_out[(size_t)s * S + a] = sends ? before : 0;
     };
     // Stage indices of the batch at position e0: lane u holds the u-th (one coalesced load),
     // v_readlane hands them out as scalars.  An entry that is no stage index is clamped.
@@ -153,28 +114,16 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
     // wait for the lot), then all stores.
     auto process = [&](const int (&ss)[U], const int (&dd)[U], const i64 (&ln)[U]) {
         i64 off[U];
-        int pos[U];
         bool sends[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             sends[u] = dd[u] >= 0 && dd[u] < S;
             const int w = (sends[u] ? dd[u] : 0) * RD_ROWS + lane;
             off[u] = (i64)atomicAdd(reinterpret_cast<u64*>(&sent[w]), (u64)(sends[u] ? ln[u] : 0));
-            if constexpr (LISTS) pos[u] = atomicAdd(&next[w], sends[u] ? 1 : 0);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const i64 o = sends[u] ? off[u] : 0;
-            if constexpr (LISTS) {
-                i64x2 entry;                     // one 16-byte store: (bytes per lane, stage)
-                entry.x = ln[u];
-                entry.y = ss[u];
-                // pos < max_stages for any permutation; everything else goes to the dump slot
-                const int slot = sends[u] && pos[u] < max_stages ? pos[u] : max_stages;
-                if (live) list[lbase + slot] = entry;
-            }
-            if (live) off_out[(size_t)ss[u] * S + a] = o;
-        }
+        for (int u = 0; u < U; ++u)
+            if (live) off_out[(size_t)ss[u] * S + a] = sends[u] ? off[u] : 0;
     };
     // Three batch buffers take the roles "being processed", "rows in flight", "indices in
     // flight" in turn, so no register is copied while its load is outstanding.
@@ -283,116 +232,266 @@ __device__ __forceinline__ i64 dpp_sum8(i64 v) {
     v += dpp_i64<0x141>(v);
     return v;
 }
-__device__ __forceinline__ int dpp_ror8(int v) {
-    return __builtin_amdgcn_update_dpp(0, v, 0x128, 0xf, 0xf, false);   // row_ror:8
-}
-__device__ __forceinline__ i64 dpp_ror8(i64 v) { return dpp_i64<0x128>(v); }
-
-// Exchange between the two 16-lane rows of each half (xor 16) and between the two halves
-// (xor 32) with the gfx950 row-swap instructions: swap(v, v) returns the pair
-// (rows 0,0,2,2 | rows 1,1,3,3) resp. (lower half twice | upper half twice), so one
-// commutative operation on the pair leaves the reduction in every lane - no LDS round trip.
-struct rd_sum { template <typename T> __device__ T operator()(T a, T b) const { return a + b; } };
-struct rd_max { template <typename T> __device__ T operator()(T a, T b) const { return a > b ? a : b; } };
-template <bool ROWS, typename OP>
-__device__ __forceinline__ int rd_swap_reduce(int v, OP op) {
-    if constexpr (ROWS) {
-        const auto r = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
-        return op((int)r[0], (int)r[1]);
-    } else {
-        const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
-        return op((int)r[0], (int)r[1]);
-    }
-}
-template <bool ROWS, typename OP>
-__device__ __forceinline__ i64 rd_swap_reduce(i64 v, OP op) {
-    const unsigned lo = (unsigned)(u64)v, hi = (unsigned)((u64)v >> 32);
-    i64 a, b;
-    if constexpr (ROWS) {
-        const auto l = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
-        const auto h = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
-        a = (i64)(((u64)h[0] << 32) | l[0]);
-        b = (i64)(((u64)h[1] << 32) | l[1]);
-    } else {
-        const auto l = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
-        const auto h = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
-        a = (i64)(((u64)h[0] << 32) | l[0]);
-        b = (i64)(((u64)h[1] << 32) | l[1]);
-    }
-    return op(a, b);
-}
 template <int CTRL> __device__ __forceinline__ int rd_dpp_get(int v) {
     return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
 }
 template <int CTRL> __device__ __forceinline__ i64 rd_dpp_get(i64 v) { return dpp_i64<CTRL>(v); }
-
-// Largest, over the 8 GPUs, of max(bytes forwarded, bytes received): m is the lane's
-// cell (k, j) of the redistribution matrix with the diagonal already zeroed.  The result is
-// in every lane.
-template <typename I>
-__device__ __forceinline__ I rd_volume(I m) {
-    const I fwd = dpp_sum8(m);                              // row k: what lane k forwards
-    I recv = m + dpp_ror8(m);                               // column j: rows k and k ^ 1 ...
-    recv = rd_swap_reduce<true>(recv, rd_sum());            // ... the other 16-lane row ...
-    recv = rd_swap_reduce<false>(recv, rd_sum());           // ... and the other half
-    I v = max(fwd, recv);
-    v = max(v, rd_dpp_get<0xB1>(v));                        // quad_perm [1,0,3,2]
-    v = max(v, rd_dpp_get<0x4E>(v));                        // quad_perm [2,3,0,1]
-    v = max(v, rd_dpp_get<0x141>(v));                       // row_half_mirror
-    v = max(v, rd_dpp_get<0x140>(v));                       // row_mirror
-    v = rd_swap_reduce<true>(v, rd_max());
-    v = rd_swap_reduce<false>(v, rd_max());
+// largest value among the 8 lanes of a group, in every lane of the group
+template <typename I> __device__ __forceinline__ I dpp_max8(I v) {
+    v = max(v, rd_dpp_get<0xB1>(v));
+    v = max(v, rd_dpp_get<0x4E>(v));
+    v = max(v, rd_dpp_get<0x141>(v));
     return v;
 }
 
-// The pair's list is in execution order, so a stage's send offset is the running sum of the
-// bytes of the entries before it.
-template <typename I>
-__device__ __forceinline__ void rd_run_pair(const i64 lo64[8], const i64 hi64[8], bool diag,
-                                            const i64x2* __restrict__ list, int n,
-                                            u64* __restrict__ redis) {
-    I lo[8], hi[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) { lo[i] = (I)lo64[i]; hi[i] = (I)hi64[i]; }
-    i64 off = 0;
-    for (int e = 0; e < n; ++e) {
-        const i64x2 entry = list[e];
-        const int s = (int)entry.y;
-        const i64 end = off + entry.x;
-        I m = rd_cell<I>(lo, hi, (I)off, (I)end);
-        off = end;
-        if (diag) m = 0;
-        const I v = rd_volume<I>(m);
-        if ((threadIdx.x & 63) == 0 && v > 0) atomicMax(&redis[s], (u64)v);
-    }
+// Threads per workgroup: the tables of a source server take 512 bytes per destination server
+// with 32-bit words, so at 128 servers a compute unit holds them once or twice; sixteen
+// wavefronts on one copy keep the unit busier than two workgroups of four on two copies.
+constexpr int RV_THREADS32 = 1024;
+constexpr int RV_THREADS64 = 256;
+constexpr int RV_BLOCK = 128;       // stages a wavefront looks at before it works on those that send
+constexpr int RV_PAIR_WORDS = 128;  // per destination server: two 8 x 8 tables
+
+// one (stage, source) that sends: destination, stage, offset and length of the chunk
+template <typename I> struct alignas(sizeof(I) == 4 ? 16 : 8) rv_entry { int d, s; I off, len; };
+
+template <typename I> inline size_t rd_volumes_lds_bytes(int S) {
+    constexpr int waves = (sizeof(I) == 4 ? RV_THREADS32 : RV_THREADS64) / 64;
+    return (size_t)S * RV_PAIR_WORDS * sizeof(I) + (size_t)waves * RV_BLOCK * sizeof(rv_entry<I>);
 }
 
-// grid (S * S, B), 64 threads: one wavefront per ordered server pair (a, d).
-__global__ void __launch_bounds__(64)
-rd_volumes(const i64* __restrict__ traffic, const i64* __restrict__ X,
-           const int32_t* __restrict__ num_stages, const int32_t* __restrict__ lstart,
-           const int32_t* __restrict__ lcnt, const i64x2* __restrict__ list,
-           u64* __restrict__ redis, int S, int G, int max_stages) {
-    __shared__ i64 t[RD_TILE_WORDS];
-    const int b = blockIdx.y;
-    const int a = blockIdx.x / S;
-    const int d = blockIdx.x - a * S;
-    if (a == d || num_stages[b] <= 0) return;
-    const size_t pair = ((size_t)b * S + a) * S + d;
-    const int n = lcnt[pair];
-    if (n <= 0) return;
+// The volumes of all stages in which source server a of matrix b sends.  I: the integer type
+// the intervals are worked out in - int when every tile of the source server has a total
+// below 2^31 (no offset, prefix sum or overlap can then exceed it), else 64-bit.  Returns false
+// (and does nothing) if I is int and the data do not fit.  All threads of the workgroup
+// (RV_THREADS32 or RV_THREADS64) call it together.
+//
+// LDS tables per destination server d, each [i][k] with rows of 8 words (unused rows and
+// columns of a cluster with fewer than 8 GPUs per server hold zeros):
+//   PX[i][k] = X[i][0] + ... + X[i][k]     (lane-routing tile of the pair, row i)
+//   CP[i][j] = t[i][0] + ... + t[i][j]     (traffic tile of the pair, row i)
+// Piece (i -> k) has X[i][k] = PX[i][k] - PX[i][k-1] bytes and starts in row i's region at
+// PX[i][k-1], plus X[i][i] if the diagonal has not been passed yet (i > k); in lane k's queue
+// the pieces follow each other - own head first, then donors in ascending order - so their
+// start is a running sum.  The part of a piece that a chunk takes is an interval of the
+// region, and what it holds for GPU j is its overlap with [CP[i][j-1], CP[i][j]).
+template <typename I>
+__device__ __forceinline__ bool
+rv_source(const i64* __restrict__ traffic, const i64* __restrict__ X,
+          const int32_t* __restrict__ stages, const i64* __restrict__ stage_bytes,
+          const i64* __restrict__ stage_offset, u64* __restrict__ redis, int K, int b, int a,
+          int S, int G, int max_stages, unsigned char* smem) {
+    constexpr int RV_THREADS = sizeof(I) == 4 ? RV_THREADS32 : RV_THREADS64;
+    constexpr int RV_WAVES = RV_THREADS / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int N = S * G;
-    const size_t tile = ((size_t)b * N + (size_t)a * G) * N + (size_t)d * G;
-    i64 lo[8], hi[8];
-    const i64 total = rd_intervals(traffic + tile, X + tile, (size_t)N, G, t, lo, hi);
-    const size_t lbase = ((size_t)b * S + a) * (size_t)(max_stages + 1) + lstart[pair];
-    const int lane = threadIdx.x & 63;
-    const bool diag = (lane >> 3) == (lane & 7);
-    u64* out = redis + (size_t)b * max_stages;
-    if (total < ((i64)1 << 31))
-        rd_run_pair<int>(lo, hi, diag, list + lbase, n, out);
-    else
-        rd_run_pair<i64>(lo, hi, diag, list + lbase, n, out);
+    I* tab = reinterpret_cast<I*>(smem);
+    rv_entry<I>* slots = reinterpret_cast<rv_entry<I>*>(tab + (size_t)S * RV_PAIR_WORDS) + wave * RV_BLOCK;
+
+    // ---- the tiles of the source server's G rows, as they are (coalesced along the rows)
+    if (G < 8) {
+        for (int e = tid; e < S * RV_PAIR_WORDS; e += RV_THREADS) tab[e] = 0;
+        __syncthreads();
+    }
+    bool bad = false;
+    for (int i = 0; i < G; ++i) {
+        const size_t row = ((size_t)b * N + (size_t)a * G + i) * N;
+        for (int c = tid; c < N; c += RV_THREADS) {
+            const int d = G == 8 ? c >> 3 : c / G;
+            const int k = c - d * G;
+            const i64 x = X[row + c], t = traffic[row + c];
+            if constexpr (sizeof(I) == 4) bad |= (((u64)x | (u64)t) >> 31) != 0;
+            tab[d * RV_PAIR_WORDS + i * 8 + k] = (I)x;
+            tab[d * RV_PAIR_WORDS + 64 + i * 8 + k] = (I)t;
+        }
+    }
+    __syncthreads();
+    // ---- prefix sums along every row, in place: thread (d, i); the 8 threads of a pair add
+    // up its total
+    for (int it = tid; it < S * 8; it += RV_THREADS) {
+        const int d = it >> 3, i = it & 7;
+        I* px = tab + d * RV_PAIR_WORDS + i * 8;
+        I* cp = px + 64;
+        i64 sx = 0, st = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            sx += (i64)px[k];
+            px[k] = (I)sx;
+            st += (i64)cp[k];
+            cp[k] = (I)st;
+        }
+        if constexpr (sizeof(I) == 4) {
+            sx = dpp_sum8(sx);
+            st = dpp_sum8(st);
+            if (d != a) bad |= ((u64)(sx | st) >> 31) != 0;
+        }
+    }
+    if (__syncthreads_or(bad ? 1 : 0)) {
+        if constexpr (sizeof(I) == 4) return false;
+    }
+
+    // ---- the stages.  A wavefront takes RV_BLOCK stages at a time, files the ones in which
+    // the source server sends (on skewed traffic most rows of a stage carry virtual bytes only)
+    // in its LDS slots, and works on eight of them at once: lane (g, k) = lane k of entry g.
+    const int grp = lane >> 3, k = lane & 7;
+    const int km = k > 0 ? k - 1 : 0;
+    const size_t base = (size_t)b * max_stages * S + a;
+    const int32_t* st = stages + base;
+    const i64* by = stage_bytes + base;
+    const i64* of = stage_offset + base;
+    // the destinations of a block are loaded one block ahead of their use (a strided walk down
+    // the column of the source server: every load is a round trip to L2 or further); offsets
+    // and lengths only where the source server sends - loading them for every stage costs more
+    // memory traffic than the wait it hides
+    constexpr int H = RV_BLOCK / 64;
+    int dn[H];
+    auto fetch = [&](int s0) {
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            const int s = s0 + h * 64 + lane;
+            dn[h] = -1;
+            if (s < K) dn[h] = st[(size_t)s * S];
+        }
+    };
+    if (wave * RV_BLOCK < K) fetch(wave * RV_BLOCK);
+    for (int s0 = wave * RV_BLOCK; s0 < K; s0 += RV_WAVES * RV_BLOCK) {
+        int dc[H];
+#pragma unroll
+        for (int h = 0; h < H; ++h) dc[h] = dn[h];
+        if (s0 + RV_WAVES * RV_BLOCK < K) fetch(s0 + RV_WAVES * RV_BLOCK);
+        int n = 0;
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            const int d = dc[h];
+            const int s = s0 + h * 64 + lane;
+            const bool act = d >= 0 && d < S && d != a;
+            const u64 m = __builtin_amdgcn_ballot_w64(act);
+            if (act) {
+                const int r = n + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32),
+                                      __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+                rv_entry<I> e;
+                e.d = d;
+                e.s = s;
+                e.off = (I)of[(size_t)s * S];
+                e.len = (I)by[(size_t)s * S];
+                slots[r] = e;
+            }
+            n += __builtin_popcountll(m);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");      // the wavefront's own slots
+        __builtin_amdgcn_wave_barrier();
+        for (int e0 = 0; e0 < n; e0 += 8) {
+            const bool valid = e0 + grp < n;
+            const rv_entry<I> e = slots[valid ? e0 + grp : n - 1];
+            const I off = e.off;
+            const I end = off + (valid && e.len > 0 ? e.len : (I)0);
+            const I* T = tab + e.d * RV_PAIR_WORDS;
+            I recv[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) recv[j] = 0;
+            // the part [ua, ub) of row i's region: what it holds for every GPU j
+            auto spread = [&](const I* cp, I ua, I ub) {
+                I c[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) c[j] = cp[j];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const I lo = j > 0 ? max(ua, c[j - 1]) : ua;
+                    const I hi = min(ub, c[j]);
+                    recv[j] += max(hi - lo, (I)0);
+                }
+            };
+            // own head first: piece (k -> k), at the start of the queue and of the region
+            I q;
+            {
+                const I* px = T + k * 8;
+                const I pk = px[k], pm = px[km];
+                q = pk - (k > 0 ? pm : (I)0);
+                const I hi = min(end, q);
+                spread(px + 64, min(off, hi), hi);
+            }
+            // then the pieces handed in, in ascending donor index
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const I* px = T + i * 8;
+                const I pk = px[k], pm0 = px[km];
+                const I pm = k > 0 ? pm0 : (I)0;
+                const I len = i == k ? (I)0 : pk - pm;
+                const I lo = max(off, q), hi = min(end, q + len);
+                const bool hit = hi > lo;
+                if (__builtin_amdgcn_ballot_w64(hit) != 0) {
+                    // a lane whose chunk misses the piece passes the empty interval [0, 0): its
+                    // own offsets are out of the piece's range and must not enter the arithmetic
+                    const I xii = px[i] - (i > 0 ? px[i - 1] : (I)0);
+                    const I ua = hit ? pm + (i > k ? xii : (I)0) + (lo - q) : (I)0;
+                    spread(px + 64, ua, hit ? ua + (hi - lo) : (I)0);
+                }
+                q += len;
+            }
+            // what the lane forwards (everything that is not for its own GPU), what every GPU
+            // is sent by the other lanes, and the largest of all
+            I fwd = 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                recv[j] = j == k ? (I)0 : recv[j];
+                fwd += recv[j];
+            }
+            I v = dpp_max8<I>(fwd);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v = max(v, dpp_sum8(recv[j]));
+            if (k == 0 && valid && v > 0) atomicMax(&redis[e.s], (u64)v);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");      // slots read before they are refilled
+        __builtin_amdgcn_wave_barrier();
+    }
+    return true;
+}
+
+// Maps a workgroup index to a (matrix, source server) item so that the 16 consecutive source
+// servers whose stage rows share cache lines run on the same XCD at about the same time
+// (workgroups are dealt to the 8 XCDs in turn, and each XCD has its own L2).
+__device__ __forceinline__ int rv_item(int idx) {
+    const int xcd = idx & 7, slot = idx >> 3;
+    return ((slot >> 4) * 8 + xcd) * 16 + (slot & 15);
+}
+inline unsigned rv_grid(int items) { return (unsigned)((items + 127) / 128 * 128); }
+
+// grid rv_grid(B * S), RV_THREADS32 threads, LDS rd_volumes_lds_bytes<int>(S): 32-bit intervals;
+// need64[b * S + a] = 1 where the source server's data do not fit (0 otherwise).
+__global__ void __launch_bounds__(RV_THREADS32)
+rd_volumes32(const i64* __restrict__ traffic, const i64* __restrict__ X,
+             const int32_t* __restrict__ stages, const i64* __restrict__ stage_bytes,
+             const i64* __restrict__ stage_offset, const int32_t* __restrict__ num_stages,
+             int32_t* __restrict__ need64, u64* __restrict__ redis, int B, int S, int G,
+             int max_stages) {
+    extern __shared__ __align__(16) unsigned char rv_smem[];
+    const int item = rv_item((int)blockIdx.x);
+    if (item >= B * S) return;
+    const int b = item / S, a = item - b * S;
+    const int K = min(num_stages[b], max_stages);
+    if (K <= 0) return;
+    const bool ok = rv_source<int>(traffic, X, stages, stage_bytes, stage_offset,
+                                   redis + (size_t)b * max_stages, K, b, a, S, G, max_stages, rv_smem);
+    if (threadIdx.x == 0) need64[item] = ok ? 0 : 1;
+}
+
+// grid <= B * S, RV_THREADS64 threads, LDS rd_volumes_lds_bytes<i64>(S): the source servers that
+// rd_volumes32 left, with 64-bit intervals.  Each workgroup goes through its share of the items.
+__global__ void __launch_bounds__(RV_THREADS64)
+rd_volumes64(const i64* __restrict__ traffic, const i64* __restrict__ X,
+             const int32_t* __restrict__ stages, const i64* __restrict__ stage_bytes,
+             const i64* __restrict__ stage_offset, const int32_t* __restrict__ num_stages,
+             const int32_t* __restrict__ need64, u64* __restrict__ redis, int B, int S, int G,
+             int max_stages) {
+    extern __shared__ __align__(16) unsigned char rv_smem[];
+    for (int item = (int)blockIdx.x; item < B * S; item += (int)gridDim.x) {
+        const int b = item / S, a = item - b * S;
+        const int K = min(num_stages[b], max_stages);
+        if (K <= 0 || need64[item] == 0) continue;      // the same for every thread
+        (void)rv_source<i64>(traffic, X, stages, stage_bytes, stage_offset,
+                             redis + (size_t)b * max_stages, K, b, a, S, G, max_stages, rv_smem);
+        __syncthreads();        // the tables are rebuilt for the next item
+    }
 }
 
 // grid (S, n_sel), 64 threads: one wavefront per (selected stage, source server).
