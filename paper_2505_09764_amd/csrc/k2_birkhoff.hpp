@@ -408,7 +408,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         // two rows and loses when it holds one.
         constexpr bool DEEP_FROM_READS = NR == 2;
         constexpr bool PAIR_FROM_READS = NR == 2;
-        enum { GO_ON = 0, DONE, GENERAL, DEEP };
+        enum { GO_ON = 0, GENERAL, DEEP };
         for (;;) {
             // ---- the stages that end in a two-level repair run in this inner loop; anything
             // else leaves it with a reason and is handled below
@@ -460,7 +460,8 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 boff += 8u * (u32)S;
                 coff += 8u;
                 Lrem -= (std::conditional_t<PAIRS, u32, i64>)c64;
-                if (__builtin_expect(Lrem == 0, 0)) { why = DONE; break; }
+                // (the stage that ends the decomposition leaves every row at zero: it takes the
+                // exit for several exhausted cells below and is told apart after the loop)
                 if constexpr (!LATE_WRITE_BACK) write_back();
                 nz = 0;
 #pragma unroll
@@ -543,7 +544,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     }
                 }
             } while (__builtin_expect(s < max_stages, 1));
-            if (why == DONE) break;
+            if (Lrem == 0) break;                           // done
             if (why == GO_ON) { status = -2; break; }       // out of stage rows
 #pragma unroll
             for (int k = 0; k < NR; ++k) loaded[k] = mr[k];     // what LDS and the registers describe
