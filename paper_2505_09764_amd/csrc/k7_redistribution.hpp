@@ -250,7 +250,9 @@ template <typename I> __device__ __forceinline__ I dpp_max8(I v) {
 constexpr int RV_THREADS32 = 1024;
 constexpr int RV_THREADS64 = 256;
 constexpr int RV_BLOCK = 128;       // stages a wavefront looks at before it works on those that send
-constexpr int RV_PAIR_WORDS = 128;  // per destination server: two 8 x 8 tables
+// per destination server: two 8 x 8 tables, and 8 words that keep the pairs of one wavefront's
+// 64 consecutive columns on different LDS banks
+constexpr int RV_PAIR_WORDS = 136;
 
 // one (stage, source) that sends: destination, stage, offset and length of the chunk
 template <typename I> struct alignas(sizeof(I) == 4 ? 16 : 8) rv_entry { int d, s; I off, len; };
@@ -288,42 +290,78 @@ rv_source(const i64* __restrict__ traffic, const i64* __restrict__ X,
     I* tab = reinterpret_cast<I*>(smem);
     rv_entry<I>* slots = reinterpret_cast<rv_entry<I>*>(tab + (size_t)S * RV_PAIR_WORDS) + wave * RV_BLOCK;
 
-    // ---- the tiles of the source server's G rows, as they are (coalesced along the rows)
-    if (G < 8) {
+    // ---- the tiles of the source server's G rows (coalesced along the rows), as prefix sums
+    bool bad = false;
+    if (G == 8) {
+        // a tile row is 8 consecutive lanes: its prefix sums by three DPP row shifts, and lane 7
+        // of the group collects the row totals of the pair's tile
+        const int k8 = tid & 7;
+        auto prefix8 = [&](i64 v) -> i64 {
+            i64 t = dpp_i64<0x111>(v);      // row_shr:1
+            v += k8 >= 1 ? t : 0;
+            t = dpp_i64<0x112>(v);          // row_shr:2
+            v += k8 >= 2 ? t : 0;
+            t = dpp_i64<0x114>(v);          // row_shr:4
+            v += k8 >= 4 ? t : 0;
+            return v;
+        };
+        for (int c = tid; c < N; c += RV_THREADS) {
+            const int d = c >> 3;
+            I* pair = tab + d * RV_PAIR_WORDS + k8;
+            i64 x[8], t[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const size_t row = ((size_t)b * N + (size_t)a * 8 + i) * N;
+                x[i] = X[row + c];
+                t[i] = traffic[row + c];
+            }
+            i64 totx = 0, tott = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if constexpr (sizeof(I) == 4) bad |= (((u64)x[i] | (u64)t[i]) >> 31) != 0;
+                const i64 px = prefix8(x[i]), cp = prefix8(t[i]);
+                pair[i * 8] = (I)px;
+                pair[64 + i * 8] = (I)cp;
+                totx += px;
+                tott += cp;
+            }
+            if constexpr (sizeof(I) == 4)
+                if (k8 == 7 && d != a) bad |= ((u64)(totx | tott) >> 31) != 0;
+        }
+    } else {
         for (int e = tid; e < S * RV_PAIR_WORDS; e += RV_THREADS) tab[e] = 0;
         __syncthreads();
-    }
-    bool bad = false;
-    for (int i = 0; i < G; ++i) {
-        const size_t row = ((size_t)b * N + (size_t)a * G + i) * N;
-        for (int c = tid; c < N; c += RV_THREADS) {
-            const int d = G == 8 ? c >> 3 : c / G;
-            const int k = c - d * G;
-            const i64 x = X[row + c], t = traffic[row + c];
-            if constexpr (sizeof(I) == 4) bad |= (((u64)x | (u64)t) >> 31) != 0;
-            tab[d * RV_PAIR_WORDS + i * 8 + k] = (I)x;
-            tab[d * RV_PAIR_WORDS + 64 + i * 8 + k] = (I)t;
+        for (int i = 0; i < G; ++i) {
+            const size_t row = ((size_t)b * N + (size_t)a * G + i) * N;
+            for (int c = tid; c < N; c += RV_THREADS) {
+                const int d = c / G;
+                const int k = c - d * G;
+                const i64 x = X[row + c], t = traffic[row + c];
+                if constexpr (sizeof(I) == 4) bad |= (((u64)x | (u64)t) >> 31) != 0;
+                tab[d * RV_PAIR_WORDS + i * 8 + k] = (I)x;
+                tab[d * RV_PAIR_WORDS + 64 + i * 8 + k] = (I)t;
+            }
         }
-    }
-    __syncthreads();
-    // ---- prefix sums along every row, in place: thread (d, i); the 8 threads of a pair add
-    // up its total
-    for (int it = tid; it < S * 8; it += RV_THREADS) {
-        const int d = it >> 3, i = it & 7;
-        I* px = tab + d * RV_PAIR_WORDS + i * 8;
-        I* cp = px + 64;
-        i64 sx = 0, st = 0;
+        __syncthreads();
+        // prefix sums along every row, in place: thread (d, i); the 8 threads of a pair add up
+        // its total
+        for (int it = tid; it < S * 8; it += RV_THREADS) {
+            const int d = it >> 3, i = it & 7;
+            I* px = tab + d * RV_PAIR_WORDS + i * 8;
+            I* cp = px + 64;
+            i64 sx = 0, st = 0;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            sx += (i64)px[k];
-            px[k] = (I)sx;
-            st += (i64)cp[k];
-            cp[k] = (I)st;
-        }
-        if constexpr (sizeof(I) == 4) {
-            sx = dpp_sum8(sx);
-            st = dpp_sum8(st);
-            if (d != a) bad |= ((u64)(sx | st) >> 31) != 0;
+            for (int k = 0; k < 8; ++k) {
+                sx += (i64)px[k];
+                px[k] = (I)sx;
+                st += (i64)cp[k];
+                cp[k] = (I)st;
+            }
+            if constexpr (sizeof(I) == 4) {
+                sx = dpp_sum8(sx);
+                st = dpp_sum8(st);
+                if (d != a) bad |= ((u64)(sx | st) >> 31) != 0;
+            }
         }
     }
     if (__syncthreads_or(bad ? 1 : 0)) {
