@@ -249,7 +249,10 @@ int fast_build_traffic_batched(fast_plan_t *plan, int B, int E, const int64_t *t
  *                      left untouched
  * stage_order[b][0..K) has to be a permutation of 0..K-1; entries outside that range are clamped
  * into it (no out-of-bounds access), and the offsets of such a matrix are unspecified.
- * Enqueued on `stream`, asynchronous; needs no workspace.
+ * Enqueued on `stream`, asynchronous.  When the batch alone would not fill the chip the walk over
+ * the stages is cut into up to 16 chunks that run side by side; their per-pair totals go through
+ * a part of the plan's workspace (at most 15 * 512 * S * ceil(S / 64) bytes per matrix),
+ * allocated at the first call and whenever more is needed.
  */
 int fast_stage_offsets_batched(fast_plan_t *plan, int B, const int32_t *stages,
                                const int64_t *stage_bytes, const int32_t *num_stages,
@@ -273,7 +276,8 @@ int fast_stage_offsets_batched(fast_plan_t *plan, int B, const int32_t *stages,
  *                      servers that receive in stage s, of max(bytes the GPU forwards to other
  *                      GPUs of its server, bytes other GPUs forward to it); entries s >= K are 0
  * Enqueued on `stream`, asynchronous; uses its own part of the plan's workspace (4 * S bytes
- * per matrix: one flag per source server), allocated at the first call and whenever B grows.
+ * per matrix: one flag per source server, plus what fast_stage_offsets_batched uses), allocated
+ * at the first call and whenever B grows.
  */
 int fast_redistribution_batched(fast_plan_t *plan, int B, const int64_t *traffic,
                                 const int64_t *rebalance, const int32_t *stages,

@@ -51,6 +51,9 @@ struct fast_plan {
     // workspace of the redistribution analysis for `rd_cap_B` matrices
     int rd_cap_B;
     int32_t* rdNeed;       // [B][S] 1 where a source server's tiles need 64-bit intervals
+    // workspace of the chunked stage walk
+    size_t rd_chunk_bytes;
+    i64* rdChunk;          // [B][C - 1][blocks][S][64] bytes sent per server pair in each chunk
     int last_B;            // B of the most recent synthesis call (0 = none)
     unsigned char* scratch_ptr;   // device address of `scratch` on the plan's device
     // timing: four events per recorded call
@@ -167,11 +170,62 @@ void launch_k1(const fast_plan* p, const synth_workspace& ws, int B, const i64* 
 
 // The stage-walk kernel: with or without a stage order, and the variant without store predicates
 // when S is a multiple of its 64 source servers per wavefront.
-typedef void (*rd_offsets_fn)(const int32_t*, const i64*, const int32_t*, const int32_t*, i64*, int, int);
+typedef void (*rd_offsets_fn)(const int32_t*, const i64*, const int32_t*, const int32_t*, const i64*,
+                              i64*, int, int);
 rd_offsets_fn rd_offsets_kernel(int S, bool ordered) {
     const bool all = S % fastk::RD_ROWS == 0;
     if (ordered) return all ? &fastk::rd_offsets<true, true> : &fastk::rd_offsets<true, false>;
     return all ? &fastk::rd_offsets<false, true> : &fastk::rd_offsets<false, false>;
+}
+
+// Chunks the stage walk of B matrices is cut into: enough wavefronts to occupy the chip (a
+// wavefront covers 64 source servers and keeps 512 * S bytes of LDS), at least 256 stages of
+// capacity per chunk, at most 16.
+int rd_chunks(const fast_plan* p, int B) {
+    const long waves = (long)B * ((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS);
+    long c = (512 + waves - 1) / waves;
+    const long by_len = p->max_stages / 256;
+    if (c > by_len) c = by_len;
+    if (c > 16) c = 16;
+    return c < 1 ? 1 : (int)c;
+}
+
+// Enqueues the send offsets of B matrices (chunk totals first when the walk is cut up).
+int launch_stage_offsets(fast_plan* p, int B, const int32_t* stages, const int64_t* stage_bytes,
+                         const int32_t* num_stages, const int32_t* stage_order,
+                         int64_t* out_stage_offset, hipStream_t stream) {
+    const int C = rd_chunks(p, B);
+    const unsigned blocks = (unsigned)((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS);
+    const size_t lds = fastk::rd_offsets_lds_bytes(p->S);
+    if (C > 1) {
+        const size_t need = (size_t)B * (C - 1) * blocks * p->S * fastk::RD_ROWS * sizeof(i64);
+        if (need > p->rd_chunk_bytes) {
+            if (p->rdChunk) (void)hipFree(p->rdChunk);
+            p->rdChunk = nullptr;
+            p->rd_chunk_bytes = 0;
+            if (hipMalloc(&p->rdChunk, need) != hipSuccess) {
+                (void)hipGetLastError();
+                p->rdChunk = nullptr;
+                return FAST_ERR_OOM;
+            }
+            p->rd_chunk_bytes = need;
+        }
+        const dim3 grid1(blocks, B, C - 1);
+        if (stage_order)
+            hipLaunchKernelGGL(fastk::rd_chunk_totals<true>, grid1, dim3(fastk::RD_ROWS), lds, stream,
+                               stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
+                               stage_order, p->rdChunk, p->S, p->max_stages);
+        else
+            hipLaunchKernelGGL(fastk::rd_chunk_totals<false>, grid1, dim3(fastk::RD_ROWS), lds, stream,
+                               stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
+                               stage_order, p->rdChunk, p->S, p->max_stages);
+    }
+    hipLaunchKernelGGL(rd_offsets_kernel(p->S, stage_order != nullptr), dim3(blocks, B, C),
+                       dim3(fastk::RD_ROWS), lds, stream, stages,
+                       reinterpret_cast<const i64*>(stage_bytes), num_stages, stage_order,
+                       C > 1 ? p->rdChunk : nullptr, reinterpret_cast<i64*>(out_stage_offset), p->S,
+                       p->max_stages);
+    return FAST_OK;
 }
 
 // Device address of `scratch` on device `dev`, which has to be the current device; looked up
@@ -298,6 +352,8 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     p->soIdx = nullptr;
     p->rd_cap_B = 0;
     p->rdNeed = nullptr;
+    p->rd_chunk_bytes = 0;
+    p->rdChunk = nullptr;
     p->last_B = 0;
     p->scratch_ptr = nullptr;
     p->timing = 0;
@@ -316,6 +372,14 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
     if (e == hipSuccess && fastk::rd_offsets_lds_bytes(S) > 48 * 1024) {
         for (int k = 0; k < 2 && e == hipSuccess; ++k)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(rd_offsets_kernel(S, k == 0)),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)fastk::rd_offsets_lds_bytes(S));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::rd_chunk_totals<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)fastk::rd_offsets_lds_bytes(S));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fastk::rd_chunk_totals<false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)fastk::rd_offsets_lds_bytes(S));
     }
@@ -510,11 +574,10 @@ int fast_stage_offsets_batched(fast_plan_t* p, int B, const int32_t* stages,
     if (!stages || !stage_bytes || !num_stages || !out_stage_offset) return FAST_ERR_INVALID_ARG;
     if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
     if (const int rc = check_device(p); rc != FAST_OK) return rc;
-    const dim3 grid((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS, B);
-    auto kern = rd_offsets_kernel(p->S, stage_order != nullptr);
-    hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S),
-                       stream, stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
-                       stage_order, reinterpret_cast<i64*>(out_stage_offset), p->S, p->max_stages);
+    if (const int rc = launch_stage_offsets(p, B, stages, stage_bytes, num_stages, stage_order,
+                                            out_stage_offset, stream);
+        rc != FAST_OK)
+        return rc;
     if (hipGetLastError() != hipSuccess) return FAST_ERR_HIP;
     return FAST_OK;
 }
@@ -548,11 +611,10 @@ int fast_redistribution_batched(fast_plan_t* p, int B, const int64_t* traffic,
     hipLaunchKernelGGL(fastk::rd_zero, dim3((unsigned)((nR + 255) / 256 < 2048 ? (nR + 255) / 256
                                                                               : 2048)),
                        dim3(256), 0, stream, redis, nR);
-    const dim3 grid((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS, B);
-    auto kern = rd_offsets_kernel(p->S, stage_order != nullptr);
-    hipLaunchKernelGGL(kern, grid, dim3(fastk::RD_ROWS), fastk::rd_offsets_lds_bytes(p->S),
-                       stream, stages, reinterpret_cast<const i64*>(stage_bytes), num_stages,
-                       stage_order, reinterpret_cast<i64*>(out_stage_offset), p->S, p->max_stages);
+    if (const int rc = launch_stage_offsets(p, B, stages, stage_bytes, num_stages, stage_order,
+                                            out_stage_offset, stream);
+        rc != FAST_OK)
+        return rc;
     // the volumes read the offsets just written (same stream): 32-bit intervals wherever a source
     // server's tiles allow it, the 64-bit kernel picks up the rest
     const int items = B * p->S;
@@ -661,6 +723,7 @@ void fast_plan_destroy(fast_plan_t* p) {
     free_spo_workspace(p);
     if (p->soKeys) (void)hipFree(p->soKeys);
     if (p->rdNeed) (void)hipFree(p->rdNeed);
+    if (p->rdChunk) (void)hipFree(p->rdChunk);
     if (p->ev) {
         for (int c = 0; c < FAST_MAX_TIMED_CALLS; ++c)
             for (int k = 0; k < 4; ++k)

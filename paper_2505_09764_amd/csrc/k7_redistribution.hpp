@@ -24,7 +24,8 @@
 //
 // rd_offsets   one thread per source server walks the stages in execution order
 //              keeping the bytes already sent to every destination in LDS: the
-//              per-stage send offsets;
+//              per-stage send offsets; the walk is cut into chunks that run side by side,
+//              each starting from the totals of the chunks before it (rd_chunk_totals);
 // rd_volumes   one workgroup per (matrix, source server) keeps, for all S destination
 //              servers, the prefix sums of the pair's lane-routing tile and traffic tile
 //              in LDS (everything the intervals above are made of), then runs through the
@@ -55,9 +56,74 @@ __global__ void __launch_bounds__(256) rd_zero(u64* __restrict__ p, size_t n) {
         p[i] = 0;
 }
 
-// grid (ceil(S / RD_ROWS), B), RD_ROWS threads.  Lane l owns source server a and the
+// The walk over the stages of a matrix is a chain, but a chain that splits: the stages (in
+// execution order) are cut into C chunks, a first kernel adds up what every chunk sends per
+// server pair, and the walk of chunk c starts from the sum of the chunks before it.  C is
+// chosen by the host so that the chip is full (a batch of 64 matrices of 128 servers has only
+// 128 wavefronts otherwise); rd_chunk_len is the number of stages per chunk.
+__host__ __device__ inline int rd_chunk_len(int K, int C) {
+    const int L = (K + C - 1) / C;
+    return (L + RD_UNROLL - 1) / RD_UNROLL * RD_UNROLL;
+}
+
+// grid (ceil(S / RD_ROWS), B, C - 1), RD_ROWS threads: what source server a sends to every
+// destination in chunk c = blockIdx.z (the last chunk's totals are not needed);
+// chunk_tot[b][c][block][d][lane].
+template <bool ORDERED>
+__global__ void __launch_bounds__(RD_ROWS)
+rd_chunk_totals(const int32_t* __restrict__ stages, const i64* __restrict__ stage_bytes,
+                const int32_t* __restrict__ num_stages, const int32_t* __restrict__ order,
+                i64* __restrict__ chunk_tot, int S, int max_stages) {
+    extern __shared__ __align__(16) unsigned char rd_smem[];
+    constexpr int U = RD_UNROLL;
+    const int b = blockIdx.y, c = blockIdx.z, C = gridDim.z + 1;
+    const int lane = threadIdx.x;
+    const int a = blockIdx.x * RD_ROWS + lane;
+    const int K = min(num_stages[b], max_stages);
+    if (K <= 0) return;
+    i64* sent = reinterpret_cast<i64*>(rd_smem);                    // [d][lane]
+    const int ac = a < S ? a : S - 1;
+    for (int d = 0; d < S; ++d) sent[d * RD_ROWS + lane] = 0;
+    const int32_t* st = stages + (size_t)b * max_stages * S;
+    const i64* by = stage_bytes + (size_t)b * max_stages * S;
+    const int32_t* ord = ORDERED ? order + (size_t)b * max_stages : nullptr;
+    const int L = rd_chunk_len(K, C);
+    const int e0 = min(K, c * L), e1 = min(K, e0 + L);
+    // 64 stages per pass: lane u holds the index of the u-th (one coalesced load, a pass ahead),
+    // v_readlane hands them out; all 128 row loads of a pass are in flight together, and the
+    // fetch-and-adds, whose result nobody reads, queue up in the LDS pipe without a wait
+    auto load_idx = [&](int e) -> int {
+        const int p = min(e + lane, K - 1);
+        if constexpr (ORDERED) return ord[p];
+        return p;
+    };
+    int iv = e0 < e1 ? load_idx(e0) : 0;
+    for (int e = e0; e < e1; e += 64) {
+        const int cur = iv;
+        if (e + 64 < e1) iv = load_idx(e + 64);
+        int dd[64];
+        i64 ln[64];
+#pragma unroll
+        for (int u = 0; u < 64; ++u) {
+            int s = __builtin_amdgcn_readlane(cur, u);
+            s = s < 0 ? 0 : (s >= K ? K - 1 : s);
+            dd[u] = e + u < e1 ? st[(size_t)s * S + ac] : -1;
+            ln[u] = by[(size_t)s * S + ac];
+        }
+#pragma unroll
+        for (int u = 0; u < 64; ++u) {
+            const bool sends = dd[u] >= 0 && dd[u] < S;
+            (void)atomicAdd(reinterpret_cast<u64*>(&sent[(sends ? dd[u] : 0) * RD_ROWS + lane]),
+                            (u64)(sends ? ln[u] : 0));
+        }
+    }
+    i64* out = chunk_tot + (((size_t)b * (C - 1) + c) * gridDim.x + blockIdx.x) * (size_t)S * RD_ROWS;
+    for (int d = 0; d < S; ++d) out[d * RD_ROWS + lane] = sent[d * RD_ROWS + lane];
+}
+
+// grid (ceil(S / RD_ROWS), B, C), RD_ROWS threads.  Lane l owns source server a and the
 // LDS column [*][l]; no two lanes share a word, so the kernel needs no barrier.
-// The walk over the stages is a chain of dependent steps (stage index -> the stage's
+// The walk over the stages of a chunk is a chain of dependent steps (stage index -> the stage's
 // row -> the running offset in LDS), so it is software-pipelined by hand: while batch n
 // of RD_UNROLL stages is processed, the rows of batch n+1 and the indices of batch n+2
 // are in flight.
@@ -66,10 +132,10 @@ template <bool ORDERED, bool ALL>
 __global__ void __launch_bounds__(RD_ROWS)
 rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_bytes,
            const int32_t* __restrict__ num_stages, const int32_t* __restrict__ order,
-           i64* __restrict__ out_offset, int S, int max_stages) {
+           const i64* __restrict__ chunk_tot, i64* __restrict__ out_offset, int S, int max_stages) {
     extern __shared__ __align__(16) unsigned char rd_smem[];
     constexpr int U = RD_UNROLL;
-    const int b = blockIdx.y;
+    const int b = blockIdx.y, c = blockIdx.z, C = gridDim.z;
     const int lane = threadIdx.x;
     const int a = blockIdx.x * RD_ROWS + lane;
     const int K = min(num_stages[b], max_stages);     // a count beyond the capacity is not trusted
@@ -77,11 +143,30 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
     i64* sent = reinterpret_cast<i64*>(rd_smem);                    // [d][lane]
     const bool live = ALL || a < S;
     const int ac = live ? a : S - 1;                                // clamped: loads stay in range
-    for (int d = 0; d < S; ++d) sent[d * RD_ROWS + lane] = 0;
+    // where the chunk starts: what the chunks before it have sent
+    // (eight destinations at a time, so that the loads of a pass are in flight together)
+    for (int d0 = 0; d0 < S; d0 += 8) {
+        i64 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = 0;
+        for (int cc = 0; cc < c; ++cc) {
+            const i64* tot = chunk_tot + (((size_t)b * (C - 1) + cc) * gridDim.x + blockIdx.x) * (size_t)S * RD_ROWS;
+            i64 x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = tot[(size_t)min(d0 + j, S - 1) * RD_ROWS + lane];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] += x[j];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (d0 + j < S) sent[(d0 + j) * RD_ROWS + lane] = v[j];
+    }
     const int32_t* st = stages + (size_t)b * max_stages * S;
     const i64* by = stage_bytes + (size_t)b * max_stages * S;
     const int32_t* ord = ORDERED ? order + (size_t)b * max_stages : nullptr;
     i64* off_out = out_offset + (size_t)b * max_stages * S;
+    const int L = C > 1 ? rd_chunk_len(K, C) : K;
+    const int e_begin = min(K, c * L), e_end = min(K, e_begin + L);
 
     // one stage: running offset of the pair (a, d) in LDS, send offset out.  Branch-free for
     // an idle row (d < 0): it adds 0 to word 0 of the lane's column.  Lanes beyond S work on a
@@ -127,26 +212,27 @@ rd_offsets(const int32_t* __restrict__ stages, const i64* __restrict__ stage_byt
     };
     // Three batch buffers take the roles "being processed", "rows in flight", "indices in
     // flight" in turn, so no register is copied while its load is outstanding.
-    const int nb = K / U;                       // full batches; the tail follows below
+    const int nb = (e_end - e_begin) / U;       // full batches; the tail follows below
+    const int eb = e_begin;
     int i0 = 0, i1 = 0, i2 = 0;
     int s0[U], s1[U], s2[U], d0[U], d1[U], d2[U];
     i64 l0[U], l1[U], l2[U];
-    if (nb > 0) { i0 = load_idx(0); load_rows(i0, s0, d0, l0); }
-    if (nb > 1) i1 = load_idx(U);
+    if (nb > 0) { i0 = load_idx(eb); load_rows(i0, s0, d0, l0); }
+    if (nb > 1) i1 = load_idx(eb + U);
     for (int n = 0; n < nb; n += 3) {
         if (n + 1 < nb) load_rows(i1, s1, d1, l1);
-        if (n + 2 < nb) i2 = load_idx((n + 2) * U);
+        if (n + 2 < nb) i2 = load_idx(eb + (n + 2) * U);
         process(s0, d0, l0);
         if (n + 1 >= nb) break;
         if (n + 2 < nb) load_rows(i2, s2, d2, l2);
-        if (n + 3 < nb) i0 = load_idx((n + 3) * U);
+        if (n + 3 < nb) i0 = load_idx(eb + (n + 3) * U);
         process(s1, d1, l1);
         if (n + 2 >= nb) break;
         if (n + 3 < nb) load_rows(i0, s0, d0, l0);
-        if (n + 4 < nb) i1 = load_idx((n + 4) * U);
+        if (n + 4 < nb) i1 = load_idx(eb + (n + 4) * U);
         process(s2, d2, l2);
     }
-    for (int e = nb * U; e < K; ++e) {
+    for (int e = eb + nb * U; e < e_end; ++e) {
         int s = ORDERED ? ord[e] : e;
         s = s < 0 ? 0 : (s >= K ? K - 1 : s);
         stage(s, st[(size_t)s * S + ac], by[(size_t)s * S + ac]);
