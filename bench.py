@@ -24,7 +24,7 @@ quoted on.  Prints ONE JSON line:
                  B = 64 occupies a quarter of the compute units by construction
   fewer_stages_variant  the same batch with a bottleneck assignment per stage
                       (fast_plan_set_matching): stage count and time of its decomposition kernel
-  all_configs    the other four benchmark configurations at their own batch sizes, 20 timed
+  all_configs    the other four benchmark configurations at their own batch sizes, 50 timed
                  calls each: schedules/s, p50/p99 per schedule, per-kernel ms, B = 1 latency
 """
 import argparse
@@ -314,7 +314,7 @@ def main():
     # `value`; small: cfg1-cfg4 take a few seconds together)
     others = None
     if args.batch is None and not args.no_all_configs:
-        others = [small_config(torch, binding, W, ci, 20, 3, dev) for ci in (1, 2, 3, 4)
+        others = [small_config(torch, binding, W, ci, 50, 3, dev) for ci in (1, 2, 3, 4)
                   if ci != args.config]
 
     stages_total = int(K.sum())
