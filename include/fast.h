@@ -70,6 +70,18 @@ int fast_plan_create(int S, int G, double link_bw_up, double link_bw_out, fast_p
 int fast_plan_max_stages(const fast_plan_t *plan);
 
 /*
+ * Allocates every part of the plan's workspace for batches of up to B matrices (B <=
+ * FAST_MAX_BATCH), so that no later call of any entry point with a batch of at most B
+ * allocates, frees or synchronises: for callers that capture the calls into a HIP graph or must
+ * keep allocation out of their steady state.  Sizes at 128 servers: about 0.5 MB per matrix
+ * for the synthesis, 0.3 MB for the SpreadOut pass, 0.2 MB for the stage order, plus at most
+ * 34 MB for the chunked stage walk.  The plan's device must be current.  May synchronise the
+ * device (it frees what it replaces); a smaller B than already reserved changes nothing.
+ * FAST_ERR_OOM leaves the plan usable with what it had or has got so far.
+ */
+int fast_plan_reserve(fast_plan_t *plan, int B);
+
+/*
  * Synthesises the schedules of B traffic matrices (B <= FAST_MAX_BATCH).  All work is
  * enqueued on `stream` (the plan's device must be current: FAST_ERR_INVALID_ARG otherwise)
  * and the call returns without synchronising; outputs are valid once the stream has

@@ -23,7 +23,7 @@ FAST_STATUS_NEGATIVE_ENTRY = -1
 FAST_STATUS_STAGE_OVERFLOW = -2
 FAST_STATUS_INTERNAL = -3
 
-EXPORTS = ("fast_plan_create", "fast_plan_max_stages", "fast_synthesize_batched",
+EXPORTS = ("fast_plan_create", "fast_plan_max_stages", "fast_plan_reserve", "fast_synthesize_batched",
            "fast_synthesize_batched_noalloc",
            "fast_plan_set_wakeup_delay", "fast_plan_set_matching", "fast_spreadout_batched", "fast_build_traffic_batched",
            "fast_stage_order_batched", "fast_stage_offsets_batched",
@@ -56,6 +56,8 @@ def lib():
         L.fast_plan_create.restype = ctypes.c_int
         L.fast_plan_max_stages.argtypes = [vp]
         L.fast_plan_max_stages.restype = ctypes.c_int
+        L.fast_plan_reserve.argtypes = [vp, ctypes.c_int]
+        L.fast_plan_reserve.restype = ctypes.c_int
         L.fast_synthesize_batched.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp]
         L.fast_synthesize_batched.restype = ctypes.c_int
         L.fast_synthesize_batched_noalloc.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp]
@@ -107,6 +109,12 @@ def fast_plan_create(S, G, link_bw_up, link_bw_out):
 
 def fast_plan_max_stages(plan):
     return lib().fast_plan_max_stages(plan)
+
+
+def fast_plan_reserve(plan, B):
+    rc = lib().fast_plan_reserve(plan, int(B))
+    if rc != FAST_OK:
+        raise FastError("fast_plan_reserve", rc)
 
 
 def fast_synthesize_batched(plan, B, traffic, out_rebalance, out_stages, out_stage_bytes,
@@ -269,6 +277,12 @@ class Synthesizer:
 
     def alloc_outputs(self, B):
         return Outputs(B, self.S, self.G, self.max_stages, self.device)
+
+    def reserve(self, B):
+        """Workspace for batches of up to B matrices: no later call allocates."""
+        import torch
+        with torch.cuda.device(self.device):
+            fast_plan_reserve(self.plan, B)
 
     def synthesize(self, traffic, out=None):
         import torch

@@ -190,6 +190,58 @@ int rd_chunks(const fast_plan* p, int B) {
     return c < 1 ? 1 : (int)c;
 }
 
+// The per-pair totals of the chunks: `units` tables of S x 64 words (one per matrix, chunk but
+// the last, and block of 64 source servers).
+int grow_chunk_workspace(fast_plan* p, size_t units) {
+    const size_t need = units * p->S * fastk::RD_ROWS * sizeof(i64);
+    if (need <= p->rd_chunk_bytes) return FAST_OK;
+    if (p->rdChunk) (void)hipFree(p->rdChunk);
+    p->rdChunk = nullptr;
+    p->rd_chunk_bytes = 0;
+    if (hipMalloc(&p->rdChunk, need) != hipSuccess) {
+        (void)hipGetLastError();
+        p->rdChunk = nullptr;
+        return FAST_ERR_OOM;
+    }
+    p->rd_chunk_bytes = need;
+    return FAST_OK;
+}
+
+// One flag per source server of B matrices (which of them need 64-bit intervals).
+int grow_rd_workspace(fast_plan* p, int B) {
+    if (B <= p->rd_cap_B) return FAST_OK;
+    if (p->rdNeed) (void)hipFree(p->rdNeed);
+    p->rdNeed = nullptr;
+    p->rd_cap_B = 0;
+    if (hipMalloc(&p->rdNeed, (size_t)B * p->S * sizeof(int32_t)) != hipSuccess) {
+        (void)hipGetLastError();
+        p->rdNeed = nullptr;
+        return FAST_ERR_OOM;
+    }
+    p->rd_cap_B = B;
+    return FAST_OK;
+}
+
+int next_pow2(int v);
+
+// Keys and indices of the stage-order sort for B matrices.
+int grow_so_workspace(fast_plan* p, int B) {
+    if (B <= p->so_cap_B) return FAST_OK;
+    const int P = next_pow2(p->max_stages);
+    if (p->soKeys) (void)hipFree(p->soKeys);
+    p->soKeys = nullptr;
+    p->so_cap_B = 0;
+    unsigned char* base = nullptr;
+    if (hipMalloc(&base, (size_t)B * P * (sizeof(i64) + sizeof(int32_t))) != hipSuccess) {
+        (void)hipGetLastError();
+        return FAST_ERR_OOM;
+    }
+    p->soKeys = reinterpret_cast<fastk::u64*>(base);
+    p->soIdx = reinterpret_cast<int32_t*>(p->soKeys + (size_t)B * P);
+    p->so_cap_B = B;
+    return FAST_OK;
+}
+
 // Enqueues the send offsets of B matrices (chunk totals first when the walk is cut up).
 int launch_stage_offsets(fast_plan* p, int B, const int32_t* stages, const int64_t* stage_bytes,
                          const int32_t* num_stages, const int32_t* stage_order,
@@ -198,18 +250,8 @@ int launch_stage_offsets(fast_plan* p, int B, const int32_t* stages, const int64
     const unsigned blocks = (unsigned)((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS);
     const size_t lds = fastk::rd_offsets_lds_bytes(p->S);
     if (C > 1) {
-        const size_t need = (size_t)B * (C - 1) * blocks * p->S * fastk::RD_ROWS * sizeof(i64);
-        if (need > p->rd_chunk_bytes) {
-            if (p->rdChunk) (void)hipFree(p->rdChunk);
-            p->rdChunk = nullptr;
-            p->rd_chunk_bytes = 0;
-            if (hipMalloc(&p->rdChunk, need) != hipSuccess) {
-                (void)hipGetLastError();
-                p->rdChunk = nullptr;
-                return FAST_ERR_OOM;
-            }
-            p->rd_chunk_bytes = need;
-        }
+        if (const int rc = grow_chunk_workspace(p, (size_t)B * (C - 1) * blocks); rc != FAST_OK)
+            return rc;
         const dim3 grid1(blocks, B, C - 1);
         if (stage_order)
             hipLaunchKernelGGL(fastk::rd_chunk_totals<true>, grid1, dim3(fastk::RD_ROWS), lds, stream,
@@ -523,19 +565,7 @@ int fast_stage_order_batched(fast_plan_t* p, int B, const int64_t* stage_bytes,
     if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
     if (const int rc = check_device(p); rc != FAST_OK) return rc;
     const int P = next_pow2(p->max_stages);
-    if (B > p->so_cap_B) {
-        if (p->soKeys) (void)hipFree(p->soKeys);
-        p->soKeys = nullptr;
-        p->so_cap_B = 0;
-        unsigned char* base = nullptr;
-        if (hipMalloc(&base, (size_t)B * P * (sizeof(i64) + sizeof(int32_t))) != hipSuccess) {
-            (void)hipGetLastError();
-            return FAST_ERR_OOM;
-        }
-        p->soKeys = reinterpret_cast<fastk::u64*>(base);
-        p->soIdx = reinterpret_cast<int32_t*>(p->soKeys + (size_t)B * P);
-        p->so_cap_B = B;
-    }
+    if (const int rc = grow_so_workspace(p, B); rc != FAST_OK) return rc;
     const int per = fastk::SO_W_THREADS / 64;
     hipLaunchKernelGGL(fastk::so_weights, dim3((P + per - 1) / per, B), dim3(fastk::SO_W_THREADS),
                        0, stream, reinterpret_cast<const i64*>(stage_bytes), num_stages,
@@ -595,17 +625,7 @@ int fast_redistribution_batched(fast_plan_t* p, int B, const int64_t* traffic,
     if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
     if (const int rc = check_device(p); rc != FAST_OK) return rc;
     const size_t M = p->max_stages;
-    if (B > p->rd_cap_B) {
-        if (p->rdNeed) (void)hipFree(p->rdNeed);
-        p->rdNeed = nullptr;
-        p->rd_cap_B = 0;
-        if (hipMalloc(&p->rdNeed, (size_t)B * p->S * sizeof(int32_t)) != hipSuccess) {
-            (void)hipGetLastError();
-            p->rdNeed = nullptr;
-            return FAST_ERR_OOM;
-        }
-        p->rd_cap_B = B;
-    }
+    if (const int rc = grow_rd_workspace(p, B); rc != FAST_OK) return rc;
     const size_t nR = (size_t)B * M;
     fastk::u64* redis = reinterpret_cast<fastk::u64*>(out_redis_bytes);
     hipLaunchKernelGGL(fastk::rd_zero, dim3((unsigned)((nR + 255) / 256 < 2048 ? (nR + 255) / 256
@@ -715,6 +735,27 @@ int fast_plan_kernel_ms(fast_plan_t* p, int call, float* out_ms) {
             return FAST_ERR_HIP;
         }
     return FAST_OK;
+}
+
+int fast_plan_reserve(fast_plan_t* p, int B) {
+    if (!p || B < 0) return FAST_ERR_INVALID_ARG;
+    if (B == 0) return FAST_OK;
+    if (B > FAST_MAX_BATCH) return FAST_ERR_UNSUPPORTED;
+    if (const int rc = check_device(p); rc != FAST_OK) return rc;
+    int rc = grow_workspace(p, B);
+    if (rc == FAST_OK) rc = grow_spo_workspace(p, B);
+    if (rc == FAST_OK) rc = grow_so_workspace(p, B);
+    if (rc == FAST_OK) rc = grow_rd_workspace(p, B);
+    if (rc == FAST_OK) {
+        // the chunk totals are the one part whose size does not grow with the batch (small
+        // batches are cut into more chunks): b matrices in C chunks need b * (C - 1) tables per
+        // block of 64 source servers, which is below 512 / blocks tables and at most 15 * b
+        const size_t blocks = (size_t)((p->S + fastk::RD_ROWS - 1) / fastk::RD_ROWS);
+        size_t units = (size_t)15 * B * blocks;
+        if (units > 512) units = 512;
+        rc = grow_chunk_workspace(p, units);
+    }
+    return rc;
 }
 
 void fast_plan_destroy(fast_plan_t* p) {

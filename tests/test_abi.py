@@ -53,6 +53,7 @@ def test_argument_checks_without_device(fastlib):
     assert fastlib.fast_plan_create(4, 9, 400e9, 50e9, ctypes.byref(h)) == b.FAST_ERR_UNSUPPORTED
     assert h.value is None
     assert fastlib.fast_plan_max_stages(None) == -1
+    assert fastlib.fast_plan_reserve(None, 4) == b.FAST_ERR_INVALID_ARG
     assert fastlib.fast_synthesize_batched(None, 1, None, None, None, None, None, None, None) == \
         b.FAST_ERR_INVALID_ARG
     assert fastlib.fast_synthesize_batched_noalloc(None, 1, None, None, None, None, None, None,
