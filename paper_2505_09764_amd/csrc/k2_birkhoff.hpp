@@ -325,6 +325,14 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         // byte offsets of the lane's first slot in the stage row being written
         u32 soff = (u32)lane * 4u, boff = (u32)lane * 8u, coff = 0;
         asm volatile("" : "+v"(coff));     // a vector register of its own: the store needs one anyway
+        // DEFER (two rows per lane, two-half cells): the DPP steps of the stage-weight minimum
+        // need two instructions between them; instead of s_nop those are the part of the previous
+        // stage's repair that the minimum does not depend on - the new columns and the new
+        // real-byte counts of the two re-matched rows - and the advance of the three store
+        // offsets, which therefore name the stage before the one being emitted until then.
+        constexpr bool DEFER = PAIRS && NR == 2;
+        const u32 stride_s = 4u * (u32)S, stride_b = 8u * (u32)S;
+        if constexpr (DEFER) { soff -= stride_s; boff -= stride_b; coff -= 8u; }
         // mr of a uniform row
         auto mr_of = [&](int a) -> int {
             if constexpr (NR == 2) {
@@ -420,10 +428,60 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
 #pragma unroll
             for (int k = 0; k < NR; ++k) ea[k] = eb[k] = 0;
             if (__builtin_expect(s >= max_stages, 0)) { status = -2; break; }
+            // DEFER: what the previous stage of this run left to do (nothing at first)
+            u64 pmA[NR], pmR[NR];
+            int pf = 0, pd1 = 0;
+            u32 pvh = 0;
+#pragma unroll
+            for (int k = 0; k < NR; ++k) pmA[k] = pmR[k] = 0;
             do {
                 V mine = (V)rv[0];
                 if constexpr (NR == 2) mine = (V)rv[1] < mine ? (V)rv[1] : mine;
-                const i64 c64 = (i64)wave_min(mine);    // stage weight: wave-uniform, fits SV
+                i64 c64;
+                if constexpr (DEFER) {
+                    u32 v = (u32)mine, tf, td, x0, x1;
+                    u32 m0 = (u32)mr[0], m1 = (u32)mr[NR - 1], l0 = (u32)rl[0], l1 = (u32)rl[NR - 1];
+                    const u32 eh0 = (u32)((u64)ea[0] >> 32), eh1 = (u32)((u64)ea[NR - 1] >> 32);
+                    const u64 mC0 = pmA[0] | pmR[0], mC1 = pmA[NR - 1] | pmR[NR - 1];
+                    asm volatile(
+                        "v_mov_b32 %[tf], %[pf]\n\t"
+                        "v_mov_b32 %[td], %[pd1]\n\t"
+                        "v_min_u32_dpp %[v], %[v], %[v] quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+                        "v_cndmask_b32_e64 %[m0], %[m0], %[td], %[mR0]\n\t"
+                        "v_cndmask_b32_e64 %[m1], %[m1], %[td], %[mR1]\n\t"
+                        "v_min_u32_dpp %[v], %[v], %[v] quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+                        "v_cndmask_b32_e64 %[m0], %[m0], %[tf], %[mA0]\n\t"
+                        "v_cndmask_b32_e64 %[m1], %[m1], %[tf], %[mA1]\n\t"
+                        "v_min_u32_dpp %[v], %[v], %[v] row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                        "v_mov_b32 %[tf], %[pvh]\n\t"
+                        "v_add_u32 %[soff], %[ds], %[soff]"
+                        : [v] "+v"(v), [tf] "=&v"(tf), [td] "=&v"(td), [m0] "+v"(m0), [m1] "+v"(m1),
+                          [soff] "+v"(soff)
+                        : [pf] "s"(pf), [pd1] "s"(pd1), [pvh] "s"(pvh), [mR0] "s"(pmR[0]),
+                          [mR1] "s"(pmR[NR - 1]), [mA0] "s"(pmA[0]), [mA1] "s"(pmA[NR - 1]),
+                          [ds] "s"(stride_s));
+                    asm volatile(
+                        "v_min_u32_dpp %[v], %[v], %[v] row_mirror row_mask:0xf bank_mask:0xf\n\t"
+                        "v_cndmask_b32_e64 %[x0], %[th], %[eh0], %[mA0]\n\t"
+                        "v_cndmask_b32_e64 %[x1], %[th], %[eh1], %[mA1]\n\t"
+                        "v_min_u32_dpp %[v], %[v], %[v] row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                        "v_cndmask_b32_e64 %[l0], %[l0], %[x0], %[mC0]\n\t"
+                        "v_cndmask_b32_e64 %[l1], %[l1], %[x1], %[mC1]\n\t"
+                        "v_min_u32_dpp %[v], %[v], %[v] row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+                        "v_add_u32 %[boff], %[db], %[boff]\n\t"
+                        "v_add_u32 %[coff], 8, %[coff]"
+                        : [v] "+v"(v), [x0] "=&v"(x0), [x1] "=&v"(x1), [l0] "+v"(l0), [l1] "+v"(l1),
+                          [boff] "+v"(boff), [coff] "+v"(coff)
+                        : [th] "v"(tf), [eh0] "v"(eh0), [eh1] "v"(eh1), [mA0] "s"(pmA[0]),
+                          [mA1] "s"(pmA[NR - 1]), [mC0] "s"(mC0), [mC1] "s"(mC1), [db] "s"(stride_b));
+                    mr[0] = (int)m0;
+                    mr[NR - 1] = (int)m1;
+                    rl[0] = (RL)l0;
+                    rl[NR - 1] = (RL)l1;
+                    c64 = (i64)rdl(v, 63);
+                } else {
+                    c64 = (i64)wave_min(mine);      // stage weight: wave-uniform, fits SV
+                }
                 // one copy of the weight in vector registers for all the per-lane arithmetic
                 SV c;
                 if constexpr (sizeof(V) == 8) {
@@ -456,9 +514,11 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 // every lane stores the same word: no divergent branch on the path
                 *reinterpret_cast<i64*>(reinterpret_cast<char*>(cw) + coff) = (i64)(std::make_unsigned_t<SV>)c << sh;
                 ++s;
-                soff += 4u * (u32)S;
-                boff += 8u * (u32)S;
-                coff += 8u;
+                if constexpr (!DEFER) {
+                    soff += stride_s;
+                    boff += stride_b;
+                    coff += 8u;
+                }
                 Lrem -= (std::conditional_t<PAIRS, u32, i64>)c64;
                 // (the stage that ends the decomposition leaves every row at zero: it takes the
                 // exit for several exhausted cells below and is told apart after the loop)
@@ -518,6 +578,20 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     vb = value_of_row(eb, a1);
                 }
                 u64 anyv = 0;
+                if constexpr (DEFER) {
+                    // the residuals now (the next minimum needs them), the rest during that minimum
+#pragma unroll
+                    for (int k = 0; k < NR; ++k) {
+                        const bool isA = lid[k] == a1, isR = lid[k] == r0;
+                        const u32 xlo = isA ? (u32)(u64)ea[k] : (u32)(u64)vb;
+                        rv[k] = (isA || isR) ? (SV)xlo : rv[k];
+                        pmA[k] = ballot(isA);
+                        pmR[k] = ballot(isR);
+                    }
+                    pf = f;
+                    pd1 = d1;
+                    pvh = (u32)((u64)vb >> 32);
+                } else {
 #pragma unroll
                 for (int k = 0; k < NR; ++k) {
                     const bool isA = lid[k] == a1, isR = lid[k] == r0;
@@ -530,6 +604,7 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     vfl[k] = ch ? fl : vfl[k];
                     anyv |= (ballot(isA) | ballot(isR)) & ballot(flag_of(x) != 0);
                     mr[k] = isA ? f : (isR ? d1 : mr[k]);
+                }
                 }
                 if (__builtin_expect(anyv != 0, 0)) {
 #pragma unroll
