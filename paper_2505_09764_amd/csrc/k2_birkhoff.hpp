@@ -439,10 +439,9 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 if constexpr (NR == 2) mine = (V)rv[1] < mine ? (V)rv[1] : mine;
                 i64 c64;
                 if constexpr (DEFER) {
-                    u32 v = (u32)mine, tf, td, x0, x1;
+                    u32 v = (u32)mine, tf, td;
                     u32 m0 = (u32)mr[0], m1 = (u32)mr[NR - 1], l0 = (u32)rl[0], l1 = (u32)rl[NR - 1];
                     const u32 eh0 = (u32)((u64)ea[0] >> 32), eh1 = (u32)((u64)ea[NR - 1] >> 32);
-                    const u64 mC0 = pmA[0] | pmR[0], mC1 = pmA[NR - 1] | pmR[NR - 1];
                     asm volatile(
                         "v_mov_b32 %[tf], %[pf]\n\t"
                         "v_mov_b32 %[td], %[pd1]\n\t"
@@ -462,18 +461,18 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                           [ds] "s"(stride_s));
                     asm volatile(
                         "v_min_u32_dpp %[v], %[v], %[v] row_mirror row_mask:0xf bank_mask:0xf\n\t"
-                        "v_cndmask_b32_e64 %[x0], %[th], %[eh0], %[mA0]\n\t"
-                        "v_cndmask_b32_e64 %[x1], %[th], %[eh1], %[mA1]\n\t"
+                        "v_cndmask_b32_e64 %[l0], %[l0], %[eh0], %[mA0]\n\t"
+                        "v_cndmask_b32_e64 %[l1], %[l1], %[eh1], %[mA1]\n\t"
                         "v_min_u32_dpp %[v], %[v], %[v] row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
-                        "v_cndmask_b32_e64 %[l0], %[l0], %[x0], %[mC0]\n\t"
-                        "v_cndmask_b32_e64 %[l1], %[l1], %[x1], %[mC1]\n\t"
+                        "v_cndmask_b32_e64 %[l0], %[l0], %[th], %[mR0]\n\t"
+                        "v_cndmask_b32_e64 %[l1], %[l1], %[th], %[mR1]\n\t"
                         "v_min_u32_dpp %[v], %[v], %[v] row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
                         "v_add_u32 %[boff], %[db], %[boff]\n\t"
                         "v_add_u32 %[coff], 8, %[coff]"
-                        : [v] "+v"(v), [x0] "=&v"(x0), [x1] "=&v"(x1), [l0] "+v"(l0), [l1] "+v"(l1),
-                          [boff] "+v"(boff), [coff] "+v"(coff)
+                        : [v] "+v"(v), [l0] "+v"(l0), [l1] "+v"(l1), [boff] "+v"(boff), [coff] "+v"(coff)
                         : [th] "v"(tf), [eh0] "v"(eh0), [eh1] "v"(eh1), [mA0] "s"(pmA[0]),
-                          [mA1] "s"(pmA[NR - 1]), [mC0] "s"(mC0), [mC1] "s"(mC1), [db] "s"(stride_b));
+                          [mA1] "s"(pmA[NR - 1]), [mR0] "s"(pmR[0]), [mR1] "s"(pmR[NR - 1]),
+                          [db] "s"(stride_b));
                     mr[0] = (int)m0;
                     mr[NR - 1] = (int)m1;
                     rl[0] = (RL)l0;
@@ -582,11 +581,12 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                     // the residuals now (the next minimum needs them), the rest during that minimum
 #pragma unroll
                     for (int k = 0; k < NR; ++k) {
-                        const bool isA = lid[k] == a1, isR = lid[k] == r0;
-                        const u32 xlo = isA ? (u32)(u64)ea[k] : (u32)(u64)vb;
-                        rv[k] = (isA || isR) ? (SV)xlo : rv[k];
+                        // (row r0 is the one row at zero: its mask is at hand)
+                        const bool isA = lid[k] == a1;
+                        const u32 xa = isA ? (u32)(u64)ea[k] : (u32)rv[k];
+                        rv[k] = zero[k] ? (SV)(u32)(u64)vb : (SV)xa;
                         pmA[k] = ballot(isA);
-                        pmR[k] = ballot(isR);
+                        pmR[k] = Z[k];
                     }
                     pf = f;
                     pd1 = d1;
