@@ -372,6 +372,12 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         // for; every lane sends the same AND to the same word (written as an instruction of its
         // own: the compiler would wrap an atomicAnd into a dozen instructions that pick one lane)
         const u32 dummy_addr = (u32)(k2_lds_data_bytes(S) + k2_lds_spare_bytes(S)) + 128u * 16u + (u32)lane * 4u;
+        u32 mbase[NR], mkeep[NR];      // word (for column 0) and bit of the lane's rows in the masks
+#pragma unroll
+        for (int k = 0; k < NR; ++k) {
+            mbase[k] = (u32)(k2_lds_data_bytes(S) + k2_lds_spare_bytes(S)) + (u32)(lid[k] >> 5) * 4u;
+            mkeep[k] = ~(1u << (lid[k] & 31));
+        }
         auto clear_edge = [&](int a, int d) {
             // lane 0 clears the bit; the other lanes send theirs to a word of their own behind the
             // masks (64 lanes on one word would be 64 serial passes through the LDS pipeline)
@@ -555,10 +561,19 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 }
                 {   // issued once the reads have been consumed (the unused operand pins it behind
                     // the candidate masks): nothing waits for it
-                    const u32 real = (u32)(k2_lds_data_bytes(S) + k2_lds_spare_bytes(S)) +
-                                     (u32)f * 16u + (u32)(r0 >> 5) * 4u;
-                    const u32 addr = lane == 0 ? real : dummy_addr;
-                    const u32 keep = ~(1u << (r0 & 31));
+                    u32 addr, keep;
+                    if constexpr (NR == 2) {
+                        // the lane that holds the exhausted row knows the word and the bit from
+                        // constants of its own and its column; the other lanes go to their dummies
+                        addr = zero[1] ? ((u32)mr[1] << 4) + mbase[1] : dummy_addr;
+                        addr = zero[0] ? ((u32)mr[0] << 4) + mbase[0] : addr;
+                        keep = zero[0] ? mkeep[0] : mkeep[1];
+                    } else {
+                        const u32 real = (u32)(k2_lds_data_bytes(S) + k2_lds_spare_bytes(S)) +
+                                         (u32)f * 16u + (u32)(r0 >> 5) * 4u;
+                        addr = lane == 0 ? real : dummy_addr;
+                        keep = ~(1u << (r0 & 31));
+                    }
                     u64 dep = c2[0];
                     if constexpr (NR == 2) dep |= c2[1];
                     asm volatile("ds_and_b32 %0, %1" : : "v"(addr), "v"(keep), "s"(dep) : "memory");
