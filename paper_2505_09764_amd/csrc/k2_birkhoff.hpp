@@ -56,9 +56,16 @@
 //   * LDS instructions complete in order and the compiler's wait for the reads of
 //     the repair also waits for whatever was issued after them, so the atomic that
 //     clears the support bit is issued once the reads have been consumed, and only
-//     lane 0 sends it to the mask word (the other lanes to a word of their own): 64
+//     one lane sends it to the mask word (the other lanes to a word of their own): 64
 //     lanes on one word are 64 serial passes that the next stage's LDS traffic would
-//     queue behind.
+//     queue behind.  With two rows per lane that lane is the one holding the
+//     exhausted row: word and bit follow from constants of its own and its column;
+//   * every instruction of the stage costs the lone wavefront three to six clocks
+//     wherever it sits, so nothing is spent on waiting by s_nop: the two instructions
+//     the hardware wants between dependent DPP steps of the minimum are the part of
+//     the previous stage's repair that the minimum does not need (new columns and
+//     real-byte counts of the two re-matched rows; only their residuals are merged
+//     first) and the advance of the store offsets.
 //
 // Canonical choices that make the result a function of the matrix alone (the
 // paper leaves them open): level-synchronous search from one unmatched row, the
