@@ -58,8 +58,8 @@
 //     clears the support bit is issued once the reads have been consumed, and only
 //     one lane sends it to the mask word (the other lanes to a word of their own): 64
 //     lanes on one word are 64 serial passes that the next stage's LDS traffic would
-//     queue behind.  With two rows per lane that lane is the one holding the
-//     exhausted row: word and bit follow from constants of its own and its column;
+//     queue behind.  That lane is the one holding the exhausted row: word and bit
+//     follow from constants of its own and its column;
 //   * every instruction of the stage costs the lone wavefront three to six clocks
 //     wherever it sits, so nothing is spent on waiting by s_nop: the two instructions
 //     the hardware wants between dependent DPP steps of the minimum are the part of
@@ -332,12 +332,12 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
         // byte offsets of the lane's first slot in the stage row being written
         u32 soff = (u32)lane * 4u, boff = (u32)lane * 8u, coff = 0;
         asm volatile("" : "+v"(coff));     // a vector register of its own: the store needs one anyway
-        // DEFER (two rows per lane, two-half cells): the DPP steps of the stage-weight minimum
+        // DEFER (two-half cells): the DPP steps of the stage-weight minimum
         // need two instructions between them; instead of s_nop those are the part of the previous
         // stage's repair that the minimum does not depend on - the new columns and the new
         // real-byte counts of the two re-matched rows - and the advance of the three store
         // offsets, which therefore name the stage before the one being emitted until then.
-        constexpr bool DEFER = PAIRS && NR == 2;
+        constexpr bool DEFER = PAIRS;
         const u32 stride_s = 4u * (u32)S, stride_b = 8u * (u32)S;
         if constexpr (DEFER) { soff -= stride_s; boff -= stride_b; coff -= 8u; }
         // mr of a uniform row
@@ -451,7 +451,38 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                 V mine = (V)rv[0];
                 if constexpr (NR == 2) mine = (V)rv[1] < mine ? (V)rv[1] : mine;
                 i64 c64;
-                if constexpr (DEFER) {
+                if constexpr (DEFER && NR == 1) {
+                    // one row per lane: ten instructions for the seven gaps, s_nop for the rest
+                    u32 v = (u32)mine, tf, td, th;
+                    u32 m0 = (u32)mr[0], l0 = (u32)rl[0];
+                    const u32 eh0 = (u32)((u64)ea[0] >> 32);
+                    asm volatile(
+                        "v_mov_b32 %[tf], %[pf]\n\t"
+                        "v_mov_b32 %[td], %[pd1]\n\t"
+                        "v_min_u32_dpp %[v], %[v], %[v] quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+                        "v_cndmask_b32_e64 %[m0], %[m0], %[td], %[mR0]\n\t"
+                        "v_mov_b32 %[th], %[pvh]\n\t"
+                        "v_min_u32_dpp %[v], %[v], %[v] quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+                        "v_cndmask_b32_e64 %[m0], %[m0], %[tf], %[mA0]\n\t"
+                        "v_add_u32 %[soff], %[ds], %[soff]\n\t"
+                        "v_min_u32_dpp %[v], %[v], %[v] row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                        "v_cndmask_b32_e64 %[l0], %[l0], %[eh0], %[mA0]\n\t"
+                        "v_add_u32 %[boff], %[db], %[boff]\n\t"
+                        "v_min_u32_dpp %[v], %[v], %[v] row_mirror row_mask:0xf bank_mask:0xf\n\t"
+                        "v_cndmask_b32_e64 %[l0], %[l0], %[th], %[mR0]\n\t"
+                        "v_add_u32 %[coff], 8, %[coff]\n\t"
+                        "v_min_u32_dpp %[v], %[v], %[v] row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                        "s_nop 1\n\t"
+                        "v_min_u32_dpp %[v], %[v], %[v] row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+                        "s_nop 1"
+                        : [v] "+v"(v), [tf] "=&v"(tf), [td] "=&v"(td), [th] "=&v"(th), [m0] "+v"(m0),
+                          [l0] "+v"(l0), [soff] "+v"(soff), [boff] "+v"(boff), [coff] "+v"(coff)
+                        : [pf] "s"(pf), [pd1] "s"(pd1), [pvh] "s"(pvh), [mR0] "s"(pmR[0]),
+                          [mA0] "s"(pmA[0]), [eh0] "v"(eh0), [ds] "s"(stride_s), [db] "s"(stride_b));
+                    mr[0] = (int)m0;
+                    rl[0] = (RL)l0;
+                    c64 = (i64)rdl(v, 63);
+                } else if constexpr (DEFER) {
                     u32 v = (u32)mine, tf, td;
                     u32 m0 = (u32)mr[0], m1 = (u32)mr[NR - 1], l0 = (u32)rl[0], l1 = (u32)rl[NR - 1];
                     const u32 eh0 = (u32)((u64)ea[0] >> 32), eh1 = (u32)((u64)ea[NR - 1] >> 32);
@@ -576,10 +607,8 @@ k2_matrix(const i64* __restrict__ wsQ, const i64* __restrict__ wsPart,
                         addr = zero[0] ? ((u32)mr[0] << 4) + mbase[0] : addr;
                         keep = zero[0] ? mkeep[0] : mkeep[1];
                     } else {
-                        const u32 real = (u32)(k2_lds_data_bytes(S) + k2_lds_spare_bytes(S)) +
-                                         (u32)f * 16u + (u32)(r0 >> 5) * 4u;
-                        addr = lane == 0 ? real : dummy_addr;
-                        keep = ~(1u << (r0 & 31));
+                        addr = zero[0] ? ((u32)mr[0] << 4) + mbase[0] : dummy_addr;
+                        keep = mkeep[0];
                     }
                     u64 dep = c2[0];
                     if constexpr (NR == 2) dep |= c2[1];
