@@ -203,11 +203,12 @@ def main():
     # stages, and a wavefront issues at most one instruction per four clock cycles, so the
     # issue slots a stage occupies (counted by rocprofv3, committed under profiles/) are its
     # floor; peak = that floor turned into stages per second, for the B wavefronts of a launch.
-    k2_slots = k2_insts = None
+    k2_slots = k2_insts = k2_traffic = None
     prof2 = os.path.join(ROOT, "profiles", f"k2_birkhoff_cfg{args.config}_stage_counters.json")
     if os.path.exists(prof2):
         pj = json.load(open(prof2))
         k2_slots, k2_insts = pj["active_quad_cycles_per_stage"], pj["instructions_per_stage"]
+        k2_traffic = pj.get("hbm_bytes_per_launch_b64") if B == w.B else None
 
     # true single-matrix latency of the same configuration
     lat = None
@@ -345,7 +346,7 @@ def main():
                      "unit": "stages/s",
                      "frac": (float(K.sum()) / (k_avg[1] * 1e-3)) / (B * CLOCK_HZ / (4.0 * k2_slots))
                      if k2_slots else None,
-                     "traffic": None,
+                     "traffic": k2_traffic, "algorithmic_bytes": k2_bytes,
                      "issue_slots_per_stage": k2_slots, "instructions_per_stage": k2_insts,
                      "wavefronts": B,
                      "note": "peak = one instruction per 4 clocks per wavefront at 2.4 GHz over the "
